@@ -1,0 +1,403 @@
+"""Pins for the CPU oracle: brute force, finite differences, closed forms, invariants, a
+library second opinion, and the counts the paper fixes.  No GPU, no HIP code."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import attention as A
+from oracle import blocks as Bk
+from oracle import masks as Mk
+from paper_2510_10620_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def mask_rows_fn(spec):
+    return lambda s, L, r0, r1: Mk.dense_rows(spec, L, r0, r1)
+
+
+SPECS = [W.MaskSpec("causal"), W.MaskSpec("window", window=5), W.MaskSpec("lambda", window=4, sink=2),
+         W.MaskSpec("causal_blockwise", window=2, sink=1, mblock=3), W.MaskSpec("shared_question")]
+
+
+def small_case(spec, lens, B, Hq, Hkv, D, seed):
+    cu = W.cu_from_lengths(lens)
+    rng = np.random.default_rng(seed)
+    T = int(cu[-1])
+    q = rng.standard_normal((T, Hq, D))
+    k = rng.standard_normal((T, Hkv, D))
+    v = rng.standard_normal((T, Hkv, D))
+    do = rng.standard_normal((T, Hq, D))
+    table = Bk.table_from_mask(mask_rows_fn(spec), cu, B)
+    ranges = W.attn_ranges(spec, cu)
+    return cu, q, k, v, do, table, ranges
+
+
+# ---------------------------------------------------------------- brute force
+def brute_forward(q, k, v, cu, spec, scale):
+    """Scalar loops straight from the definition, with the mask taken from the formula."""
+    T, Hq, D = q.shape
+    G = Hq // k.shape[1]
+    O = np.zeros((T, Hq, D))
+    LSE = np.full((Hq, T), -math.inf)
+    for s in range(len(cu) - 1):
+        b, e = int(cu[s]), int(cu[s + 1])
+        M = Mk.dense_rows(spec, e - b)
+        for h in range(Hq):
+            for i in range(b, e):
+                sc = {}
+                for j in range(b, e):
+                    if M[i - b, j - b]:
+                        sc[j] = scale * sum(q[i, h, d] * k[j, h // G, d] for d in range(D))
+                if not sc:
+                    continue
+                z = sum(math.exp(x) for x in sc.values())
+                LSE[h, i] = math.log(z)
+                for j, x in sc.items():
+                    p = math.exp(x) / z
+                    for d in range(D):
+                        O[i, h, d] += p * v[j, h // G, d]
+    return O, LSE
+
+
+@pytest.mark.parametrize("spec", SPECS, ids=lambda s: s.kind)
+def test_forward_matches_brute_force(spec):
+    cu, q, k, v, do, table, ranges = small_case(spec, [7, 9], 3, 2, 1, 4, seed=11)
+    vis = Bk.Visibility(cu, 3, table, ranges)
+    O, LSE = A.attention_fwd(q, k, v, cu, vis, 0.5, row_chunk=4)
+    Ob, Lb = brute_forward(q, k, v, cu, spec, 0.5)
+    np.testing.assert_allclose(O, Ob, atol=1e-12)
+    np.testing.assert_allclose(LSE, Lb, atol=1e-12)
+
+
+@pytest.mark.parametrize("spec", SPECS, ids=lambda s: s.kind)
+def test_backward_matches_finite_differences(spec):
+    cu, q, k, v, do, table, ranges = small_case(spec, [6, 5], 2, 2, 1, 3, seed=5)
+    vis = Bk.Visibility(cu, 2, table, ranges)
+    scale = 0.7
+    dq, dk, dv = A.attention_bwd(q, k, v, do, cu, vis, scale, row_chunk=3)
+
+    def loss(qq, kk, vv):
+        O, _ = brute_forward(qq, kk, vv, cu, spec, scale)
+        return float((O * do).sum())
+
+    eps = 1e-6
+    for name, x, g in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        fd = np.zeros_like(x)
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += eps
+            xm[idx] -= eps
+            args_p = [q, k, v]
+            args_m = [q, k, v]
+            pos = "qkv".index(name)
+            args_p[pos], args_m[pos] = xp, xm
+            fd[idx] = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+        np.testing.assert_allclose(g, fd, atol=2e-8, err_msg=name)
+
+
+# ---------------------------------------------------------------- invariants
+def test_softmax_rows_sum_to_one_and_empty_rows():
+    S = np.random.default_rng(0).standard_normal((9, 13)) * 5
+    S[3] = -np.inf
+    S[5, 4:] = -np.inf
+    lse, P = A._softmax_rows(S)
+    rows = np.delete(np.arange(9), 3)
+    np.testing.assert_allclose(P[rows].sum(axis=1), 1.0, atol=1e-12)
+    assert lse[3] == -np.inf and not P[3].any() and not np.isnan(P).any()
+    np.testing.assert_allclose(lse[rows], np.log(np.exp(S[rows]).sum(axis=1)), atol=1e-12)
+
+
+def test_merge_of_per_kv_block_partials_is_unsplit_attention():
+    spec = W.MaskSpec("causal")
+    cu, q, k, v, do, table, ranges = small_case(spec, [37, 50], 8, 4, 2, 8, seed=3)
+    vis = Bk.Visibility(cu, 8, table, ranges)
+    O, LSE = A.attention_fwd(q, k, v, cu, vis, 0.3)
+    part = Bk.block_partition(cu, 8)
+    n_blk = len(part["blk_seq"])
+    T = int(cu[-1])
+    Om, Lm = np.zeros_like(O), np.full_like(LSE, -np.inf)
+    for qb in range(n_blk):
+        ents = [e for e in range(len(table)) if table[e, 0] == qb]
+        r0, r1 = int(part["blk_start"][qb]), int(part["blk_end"][qb])
+        ops, lps = [], []
+        for e in ents:
+            vs = Bk.Visibility(cu, 8, table, ranges, select=[e])
+            s = int(part["blk_seq"][qb])
+            Oe, Le = A.attention_fwd(q, k, v, cu, vs, 0.3, seqs=[s])
+            ops.append(Oe[r0:r1])
+            lps.append(Le[:, r0:r1])
+        rng = np.random.default_rng(qb)
+        order = rng.permutation(len(ents))
+        o1, l1 = A.merge_partials(np.stack([ops[i] for i in order]), np.stack([lps[i] for i in order]))
+        Om[r0:r1], Lm[:, r0:r1] = o1, l1
+        if len(ents) >= 3:  # merge tree: ((a,b),c...) == flat
+            oa, la = A.merge_partials(np.stack(ops[:2]), np.stack(lps[:2]))
+            ob, lb = A.merge_partials(np.stack([oa] + ops[2:]), np.stack([la] + lps[2:]))
+            np.testing.assert_allclose(ob, o1, atol=1e-12)
+            np.testing.assert_allclose(lb, l1, atol=1e-12)
+        # a partial with LSE = -inf changes nothing
+        o2, l2 = A.merge_partials(np.stack(ops + [np.full_like(ops[0], 7.0)]),
+                                  np.stack(lps + [np.full_like(lps[0], -np.inf)]))
+        np.testing.assert_allclose(o2, o1, atol=1e-12)
+        np.testing.assert_allclose(l2, l1, atol=1e-12)
+    np.testing.assert_allclose(Om, O, atol=1e-12)
+    np.testing.assert_allclose(Lm, LSE, atol=1e-12)
+    assert T == 87
+
+
+def test_merge_all_empty():
+    o, l = A.merge_partials(np.ones((3, 4, 2, 5)), np.full((3, 2, 4), -np.inf))
+    assert not o.any() and np.all(l == -np.inf)
+
+
+def test_fully_masked_blocks_contribute_nothing():
+    """SKIP entries and CAUSAL entries above the diagonal leave the result bit-identical."""
+    cu = W.cu_from_lengths([20, 13])
+    spec = W.MaskSpec("causal")
+    _, q, k, v, do, table, ranges = small_case(spec, [20, 13], 4, 2, 2, 4, seed=8)
+    dense = Bk.dense_causal_table(cu, 4)                 # includes kv_blk > q_blk, tagged CAUSAL
+    skip = table.copy()
+    extra = np.array([[0, 4, W.MASK_SKIP], [5, 6, W.MASK_SKIP]], dtype=np.int32)
+    with_skip = np.concatenate([skip, extra])
+    res = []
+    for t in (table, dense, with_skip):
+        vis = Bk.Visibility(cu, 4, t, ranges)
+        O, L = A.attention_fwd(q, k, v, cu, vis, 0.5)
+        g = A.attention_bwd(q, k, v, do, cu, vis, 0.5)
+        res.append((O, L) + g)
+    for r in res[1:]:
+        for a, b in zip(res[0], r):
+            assert np.array_equal(a, b)
+
+
+def test_library_second_opinion_sdpa_and_autograd():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(21)
+    L, H, D = 33, 2, 8
+    cu = W.cu_from_lengths([L])
+    q, k, v, do = (rng.standard_normal((L, H, D)) for _ in range(4))
+    table = Bk.table_from_mask(lambda s, L_, r0, r1: np.ones((r1 - r0, L_), bool), cu, 8)
+    assert (table[:, 2] == W.MASK_NONE).all()
+    vis = Bk.Visibility(cu, 8, table)
+    scale = 1 / math.sqrt(D)
+    O, LSE = A.attention_fwd(q, k, v, cu, vis, scale)
+    dq, dk, dv = A.attention_bwd(q, k, v, do, cu, vis, scale)
+    tq, tk, tv = (torch.tensor(x.transpose(1, 0, 2), dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    to = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)
+    to.backward(torch.tensor(do.transpose(1, 0, 2)))
+    np.testing.assert_allclose(O, to.detach().numpy().transpose(1, 0, 2), atol=1e-12)
+    for g, t in ((dq, tq), (dk, tk), (dv, tv)):
+        np.testing.assert_allclose(g, t.grad.numpy().transpose(1, 0, 2), atol=1e-12)
+    ref_lse = torch.logsumexp(scale * tq @ tk.transpose(1, 2), dim=-1).detach().numpy()
+    np.testing.assert_allclose(LSE, ref_lse, atol=1e-12)
+    # causal, GQA, autograd on an explicit masked softmax
+    cu2 = W.cu_from_lengths([L])
+    ctab = Bk.table_from_mask(mask_rows_fn(W.MaskSpec("causal")), cu2, 8)
+    vis2 = Bk.Visibility(cu2, 8, ctab)
+    k1, v1 = k[:, :1], v[:, :1]
+    O2, _ = A.attention_fwd(q, k1, v1, cu2, vis2, scale)
+    g2 = A.attention_bwd(q, k1, v1, do, cu2, vis2, scale)
+    tk1, tv1 = (torch.tensor(x.transpose(1, 0, 2), dtype=torch.float64, requires_grad=True) for x in (k1, v1))
+    tq2 = torch.tensor(q.transpose(1, 0, 2), dtype=torch.float64, requires_grad=True)
+    to2 = torch.nn.functional.scaled_dot_product_attention(tq2, tk1.expand(2, -1, -1), tv1.expand(2, -1, -1), is_causal=True)
+    to2.backward(torch.tensor(do.transpose(1, 0, 2)))
+    np.testing.assert_allclose(O2, to2.detach().numpy().transpose(1, 0, 2), atol=1e-12)
+    for g, t in zip(g2, (tq2, tk1, tv1)):
+        np.testing.assert_allclose(g, t.grad.numpy().transpose(1, 0, 2), atol=1e-12)
+
+
+# ---------------------------------------------------------------- closed forms
+def visible_counts(spec, L):
+    i = np.arange(L)
+    if spec.kind == "causal":
+        return i + 1
+    if spec.kind == "window":
+        return np.minimum(i + 1, spec.window)
+    if spec.kind == "lambda":
+        return np.minimum(i + 1, spec.window) + np.minimum(spec.sink, np.maximum(i - spec.window + 1, 0))
+    raise ValueError
+
+
+@pytest.mark.parametrize("spec", [W.MaskSpec("causal"), W.MaskSpec("window", window=37),
+                                  W.MaskSpec("lambda", window=29, sink=6)], ids=lambda s: s.kind)
+def test_closed_form_q_zero_uniform_softmax(spec):
+    """Q = 0 makes P uniform on the visible set: LSE = ln n_i, O = mean of visible V,
+    dV_j = sum_{i sees j} dO_i / n_i, dK = 0."""
+    lens, B, Hq, Hkv, D = [101, 64, 77], 16, 4, 2, 8
+    cu, q, k, v, do, table, ranges = small_case(spec, lens, B, Hq, Hkv, D, seed=2)
+    q[:] = 0
+    vis = Bk.Visibility(cu, B, table, ranges)
+    O, LSE = A.attention_fwd(q, k, v, cu, vis, 0.2)
+    dq, dk, dv = A.attention_bwd(q, k, v, do, cu, vis, 0.2)
+    for s in range(len(lens)):
+        b, e = int(cu[s]), int(cu[s + 1])
+        n = visible_counts(spec, e - b)
+        np.testing.assert_allclose(LSE[:, b:e], np.broadcast_to(np.log(n), (Hq, e - b)), atol=1e-12)
+        M = Mk.dense_rows(spec, e - b)
+        for h in range(Hq):
+            mean_v = (M / n[:, None]) @ v[b:e, h // 2]
+            np.testing.assert_allclose(O[b:e, h], mean_v, atol=1e-12)
+        for g in range(Hkv):
+            ref = sum((M / n[:, None]).T @ do[b:e, h] for h in (2 * g, 2 * g + 1))
+            np.testing.assert_allclose(dv[b:e, g], ref, atol=1e-12)
+    np.testing.assert_allclose(dk, 0, atol=1e-12)
+
+
+def test_closed_form_identical_keys():
+    """All K rows of a sequence equal: every visible score is s_i = scale q_i.k, so
+    LSE_i = s_i + ln n_i and P is uniform again (nonzero scores exercised)."""
+    spec = W.MaskSpec("causal")
+    cu, q, k, v, do, table, ranges = small_case(spec, [45, 30], 8, 2, 1, 4, seed=4)
+    for s in range(2):
+        k[cu[s]:cu[s + 1]] = k[cu[s]]
+    vis = Bk.Visibility(cu, 8, table, ranges)
+    O, LSE = A.attention_fwd(q, k, v, cu, vis, 0.9)
+    for s in range(2):
+        b, e = int(cu[s]), int(cu[s + 1])
+        n = np.arange(1, e - b + 1)
+        for h in range(2):
+            si = 0.9 * q[b:e, h] @ k[b, 0]
+            np.testing.assert_allclose(LSE[h, b:e], si + np.log(n), atol=1e-12)
+            np.testing.assert_allclose(O[b:e, h], np.cumsum(v[b:e, 0], axis=0) / n[:, None], atol=1e-12)
+
+
+def test_backward_invariants():
+    spec = W.MaskSpec("lambda", window=9, sink=3)
+    cu, q, k, v, do, table, ranges = small_case(spec, [40, 23], 8, 4, 2, 8, seed=9)
+    vis = Bk.Visibility(cu, 8, table, ranges)
+    dq, dk, dv = A.attention_bwd(q, k, v, do, cu, vis, 0.4)
+    # rows of P sum to one => column sums of dV equal the group's summed dO
+    for s in range(2):
+        b, e = int(cu[s]), int(cu[s + 1])
+        for g in range(2):
+            np.testing.assert_allclose(dv[b:e, g].sum(axis=0), do[b:e, 2 * g:2 * g + 2].sum(axis=(0, 1)), atol=1e-10)
+    # softmax is shift invariant: adding c * k-independent vector to all keys of a sequence leaves O
+    # unchanged, hence sum_j dK_j = 0 per (sequence, kv head)
+    for s in range(2):
+        b, e = int(cu[s]), int(cu[s + 1])
+        np.testing.assert_allclose(dk[b:e].sum(axis=0), 0, atol=1e-10)
+    # Delta from the final O equals rowsum(P * dP)
+    O, _ = A.attention_fwd(q, k, v, cu, vis, 0.4)
+    dl = A.delta_rows(O, do)
+    dq2, dk2, dv2 = A.attention_bwd(q, k, v, do, cu, vis, 0.4, delta=dl)
+    np.testing.assert_allclose(dq2, dq, atol=1e-12)
+    np.testing.assert_allclose(dk2, dk, atol=1e-12)
+
+
+# ---------------------------------------------------------------- block generation
+def _golden_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "block_counts.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            rows.append([c.strip() for c in line.split("|")])
+    return rows
+
+
+@pytest.mark.parametrize("row", _golden_rows(), ids=lambda r: r[0])
+def test_block_counts_fixed_by_the_paper(row):
+    name, lens, B, mask, expected = row[0], [int(x) for x in row[1].split(",")], int(row[2]), row[3], int(row[4])
+    cu = W.cu_from_lengths(lens)
+    part = Bk.block_partition(cu, B)
+    n_data = len(part["blk_seq"])
+    if name.startswith("data_blocks"):
+        assert n_data == expected
+    elif name.startswith("hyperedges"):
+        assert 3 * n_data == expected
+    else:
+        spec = W.MaskSpec(mask)
+        table = Bk.table_from_mask(mask_rows_fn(spec), cu, B)
+        assert len(table) == expected
+
+
+@pytest.mark.parametrize("spec", [W.MaskSpec("causal"), W.MaskSpec("window", window=50),
+                                  W.MaskSpec("lambda", window=40, sink=7),
+                                  W.MaskSpec("causal_blockwise", window=2, sink=1, mblock=16),
+                                  W.MaskSpec("shared_question")], ids=lambda s: s.kind)
+def test_table_defined_mask_equals_formula_mask(spec):
+    """Two independent routes to M: the mask formula, and table + per-token ranges."""
+    rng = np.random.default_rng(17)
+    lens = [int(x) for x in rng.integers(20, 200, size=4)]
+    B = 16
+    cu = W.cu_from_lengths(lens)
+    table = Bk.table_from_mask(mask_rows_fn(spec), cu, B)
+    ranges = W.attn_ranges(spec, cu)
+    vis = Bk.Visibility(cu, B, table, ranges)
+    total = 0
+    for s, L in enumerate(lens):
+        M = Mk.dense_rows(spec, L)
+        assert np.array_equal(vis.rows(s, 0, L), M)
+        total += int(M.sum())
+        # ranges lie inside the query's own sequence
+        r = ranges[cu[s]:cu[s + 1]].astype(np.int64)
+        nonempty = r[:, [1, 3]] > r[:, [0, 2]]
+        assert (r[:, [0, 2]][nonempty] >= cu[s]).all() and (r[:, [1, 3]][nonempty] <= cu[s + 1]).all()
+    assert int(vis.pair_counts().sum()) == total
+    # all-zero tiles are never constructed; every listed tile has a visible pair
+    assert (vis.pair_counts() > 0).all()
+
+
+def test_block_partition_ragged():
+    cu = W.cu_from_lengths([5, 8, 1])
+    p = Bk.block_partition(cu, 4)
+    assert p["seq_first_blk"].tolist() == [0, 2, 4, 5]
+    assert p["blk_start"].tolist() == [0, 4, 5, 9, 13]
+    assert p["blk_end"].tolist() == [4, 5, 9, 13, 14]
+    assert p["blk_seq"].tolist() == [0, 0, 1, 1, 2]
+
+
+def test_group_entries_csr():
+    table = np.array([[2, 0, 0], [0, 0, 1], [2, 2, 1], [1, 0, 3], [2, 1, 0], [1, 1, 1]], dtype=np.int32)
+    ptr, idx = Bk.group_entries(table, 0, 3)
+    assert ptr.tolist() == [0, 1, 2, 5] and idx.tolist() == [1, 5, 0, 4, 2]
+    ptr, idx = Bk.group_entries(table, 1, 3)
+    assert ptr.tolist() == [0, 2, 4, 5] and idx.tolist() == [1, 0, 5, 4, 2]
+
+
+# ---------------------------------------------------------------- shares (one device of a plan)
+def test_shares_partition_the_pairs_and_recombine():
+    spec = W.MaskSpec("causal")
+    lens, B, Hq, Hkv, D = [70, 45, 90], 16, 2, 1, 4
+    cu, q, k, v, do, table, ranges = small_case(spec, lens, B, Hq, Hkv, D, seed=13)
+    n = len(table)
+    vis_full = Bk.Visibility(cu, B, table, ranges)
+    O, LSE = A.attention_fwd(q, k, v, cu, vis_full, 0.5)
+    dq, dk, dv = A.attention_bwd(q, k, v, do, cu, vis_full, 0.5)
+    delta = A.delta_rows(O, do)
+    shares = [W.deal_share(n, 8, 205, s) for s in range(8)]
+    assert sorted(np.concatenate(shares).tolist()) == list(range(n))
+    ops, lps, gq, gk, gv = [], [], 0, 0, 0
+    for sel in shares:
+        vs = Bk.Visibility(cu, B, table, ranges, select=sel)
+        o_s, l_s = A.attention_fwd(q, k, v, cu, vs, 0.5)
+        ops.append(o_s)
+        lps.append(l_s)
+        a, b, c = A.attention_bwd(q, k, v, do, cu, vs, 0.5, lse=LSE, delta=delta)
+        gq, gk, gv = gq + a, gk + b, gv + c
+    om, lm = A.merge_partials(np.stack(ops), np.stack(lps))
+    np.testing.assert_allclose(om, O, atol=1e-12)
+    np.testing.assert_allclose(lm, LSE, atol=1e-12)
+    np.testing.assert_allclose(gq, dq, atol=1e-12)
+    np.testing.assert_allclose(gk, dk, atol=1e-12)
+    np.testing.assert_allclose(gv, dv, atol=1e-12)
+    # divisions of one share: slots are (division, q_blk) pairs
+    sel = shares[0]
+    slot, n_slots, slot_q = W.deal_divisions(table[sel, 0], 4, 305)
+    assert n_slots == len(set(zip(slot.tolist(), table[sel, 0].tolist())))
+    assert all(slot_q[slot[i]] == table[sel[i], 0] for i in range(len(sel)))
+
+
+def test_bf16_rounding_helper_is_nearest_even_and_exact_on_widening():
+    torch = pytest.importorskip("torch")
+    x = np.random.default_rng(0).standard_normal(4096).astype(np.float32) * 3
+    x[:4] = [1.0, 1.00390625, 1.01171875, -0.0]     # ties
+    bits = W.f32_to_bf16_bits(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16)
+    assert np.array_equal(bits.view(np.int16), ref.view(torch.int16).numpy())
+    assert np.array_equal(W.bf16_bits_to_f64(bits), ref.to(torch.float64).numpy())
