@@ -1,0 +1,196 @@
+/*
+ * dcp.h -- C ABI of libdcp_attn.so: the per-device hot path of Dynamic Context Parallelism
+ * (DCP): blockwise attention over packed variable-length sequences driven by a block table,
+ * the LSE-carrying merge of partial outputs, and the backward pass, for AMD gfx950.
+ *
+ * General rules
+ *   - Every function returns a dcp_status_t; nothing throws across this boundary.  On any
+ *     error no kernel is launched and no output is touched; dcp_last_error() then returns a
+ *     human-readable message (thread-local storage owned by the library).
+ *   - "host" pointers are read during the call and may be freed on return.  "device" pointers
+ *     are HIP device memory owned by the caller; the library never frees or keeps them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Launching calls only
+ *     enqueue work on it and return without synchronising.
+ *   - Tensors: q, out, dout, dq are [T, Hq, D]; k, v, dk, dv are [T, Hkv, D]; D is contiguous;
+ *     token and head strides are given in elements.  lse and delta are float [Hq, T] contiguous.
+ *     Query head h reads KV head h / (Hq / Hkv).  T = cu_seqlens[n_seq] packed tokens.
+ *
+ * Block numbering (Sec. 4.1 "Block Generation" of the paper): sequence s with L_s tokens is
+ * cut into ceil(L_s / block_size) data blocks, the last possibly short; blocks never straddle
+ * sequences; global block id = (blocks of earlier sequences) + index inside the sequence.
+ * A block-table row (q_blk, kv_blk, mask_kind) is one computation block: "attention between
+ * query block Q_i and key-value block KV_j, contributing to output block O_i" (Sec. 4.1).  It
+ * applies to every head.  The table DEFINES the mask: a (query, key) pair is visible iff a listed
+ * row covers it and the row's predicate holds; pairs not listed are not visible.
+ */
+#ifndef DCP_H_
+#define DCP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DCP_OK = 0,
+  DCP_ERR_INVALID_ARG = -1,    /* NULL pointer, negative size, bad stride, missing ranges ...   */
+  DCP_ERR_BAD_CU_SEQLENS = -2, /* cu_seqlens[0] != 0 or not strictly increasing                 */
+  DCP_ERR_BAD_TABLE = -3,      /* block id out of range, blocks of two sequences, duplicate row, */
+                               /* bad mask_kind, inconsistent output slot                        */
+  DCP_ERR_UNSUPPORTED = -4,    /* head_dim / dtype / head ratio no kernel covers                 */
+  DCP_ERR_WORKSPACE = -5,      /* workspace NULL or too small                                    */
+  DCP_ERR_HIP = -6             /* a HIP runtime call failed (message holds hipGetErrorString)    */
+} dcp_status_t;
+
+/* Predicate of one table row for query i and key j of the same sequence:
+ *   NONE   every pair of the tile is visible;
+ *   CAUSAL visible iff position(j) <= position(i);
+ *   RANGES visible iff packed index of j lies in [r[i][0], r[i][1]) or [r[i][2], r[i][3]) -- the
+ *          paper's "arrays specifying the index ranges each token should attend to, at most two
+ *          ranges per token" (Sec. 5, Blockwise Attention); r is int32 [T, 4], packed-token
+ *          coordinates, half open, an empty range has hi <= lo;
+ *   SKIP   never (the row is ignored).                                                         */
+typedef enum { DCP_MASK_NONE = 0, DCP_MASK_CAUSAL = 1, DCP_MASK_RANGES = 2, DCP_MASK_SKIP = 3 } dcp_mask_kind_t;
+
+typedef enum { DCP_BF16 = 0, DCP_F32 = 1 } dcp_dtype_t;
+
+/* Which kernel family runs.  AUTO picks MFMA when (dtype, D) is covered, else SCALAR. */
+typedef enum { DCP_IMPL_AUTO = 0, DCP_IMPL_SCALAR = 1, DCP_IMPL_MFMA = 2 } dcp_impl_t;
+
+typedef struct dcp_plan dcp_plan_t; /* opaque; created and destroyed by the library */
+
+/* ---------------------------------------------------------------------------------------------
+ * Block generation (Sec. 4.1): from per-token range arrays build the block table.  A computation
+ * block is emitted for every same-sequence (q_blk, kv_blk) whose mask tile is not all zeros
+ * ("those blocks will not be constructed"), classified NONE (all ones), CAUSAL (tile equals the
+ * causal predicate) or RANGES, in ascending (q_blk, kv_blk) order.
+ *   cu_seqlens_host  host int32[n_seq+1]
+ *   attn_ranges_host host int32[T,4]
+ *   table_out        host int32[capacity,3] or NULL (count only)
+ *   n_entries_out    receives the number of rows the full table has
+ * Returns DCP_ERR_INVALID_ARG if capacity is too small (n_entries_out is still set).  Host only. */
+dcp_status_t dcp_build_block_table(const int32_t* cu_seqlens_host, int32_t n_seq, int32_t block_size,
+                                   const int32_t* attn_ranges_host, int32_t* table_out,
+                                   int64_t capacity, int64_t* n_entries_out);
+
+/* Visible (query, key) pairs of every table row taken alone (the unit of the paper's FLOP
+ * accounting for a computation block, Sec. 4.2 vertex weights).  attn_ranges_host may be NULL if
+ * no row is RANGES.  pairs_out: host int64[n_entries].  Host only. */
+dcp_status_t dcp_count_pairs(const int32_t* cu_seqlens_host, int32_t n_seq, int32_t block_size,
+                             const int32_t* table_host, int64_t n_entries,
+                             const int32_t* attn_ranges_host, int64_t* pairs_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * Plan: the executor's per-iteration state (Sec. 3.2: the plan is set once per iteration and
+ * shared by all layers).  Validates the table, derives block token ranges, groups rows by output
+ * (forward, dQ) and by kv_blk (dK/dV), and orders work longest-first.  Host work only; device
+ * copies of the integer arrays are made on the first launch that needs them and freed by
+ * dcp_plan_destroy.
+ *   table_host    host int32[n_entries,3] rows (q_blk, kv_blk, mask_kind)
+ *   out_slot_host host int32[n_entries] or NULL.  NULL: one output per q_blk, written to the
+ *                 packed `out`/`lse`.  Otherwise row e accumulates into partial slot out_slot[e]
+ *                 (0 <= slot < n_slots); all rows of a slot must share one q_blk ("intermediate
+ *                 results pending for reduction", Sec. 5), merged later by dcp_merge_partials.
+ * n_entries == 0 is legal.  Errors: BAD_CU_SEQLENS, BAD_TABLE, INVALID_ARG. */
+dcp_status_t dcp_plan_create(dcp_plan_t** plan, const int32_t* cu_seqlens_host, int32_t n_seq,
+                             int32_t block_size, const int32_t* table_host, int64_t n_entries,
+                             const int32_t* out_slot_host, int32_t n_slots);
+dcp_status_t dcp_plan_destroy(dcp_plan_t* plan);
+
+typedef enum {
+  DCP_EXPORT_BLK_START = 0, /* [n_blocks] packed token index of each block's first token        */
+  DCP_EXPORT_BLK_LEN = 1,   /* [n_blocks]                                                        */
+  DCP_EXPORT_BLK_SEQ = 2,   /* [n_blocks] sequence of each block                                 */
+  DCP_EXPORT_FWD_PTR = 3,   /* [n_units+1] CSR over output units (q_blk, or slot when slots used)*/
+  DCP_EXPORT_FWD_IDX = 4,   /* [n_kept] table row numbers, per unit ascending kv_blk, stable     */
+  DCP_EXPORT_BWDQ_PTR = 5,  /* [n_blocks+1] CSR by q_blk                                         */
+  DCP_EXPORT_BWDQ_IDX = 6,  /* [n_kept] per q_blk ascending kv_blk, stable                       */
+  DCP_EXPORT_BWDKV_PTR = 7, /* [n_blocks+1] CSR by kv_blk                                        */
+  DCP_EXPORT_BWDKV_IDX = 8, /* [n_kept] per kv_blk ascending q_blk, stable                       */
+  DCP_EXPORT_SLOT_QBLK = 9, /* [n_slots] q_blk of each slot, -1 for a slot no row uses           */
+  DCP_EXPORT_MERGE_PTR = 10,/* [n_blocks+1] CSR: slots of each q_blk                             */
+  DCP_EXPORT_MERGE_IDX = 11 /* [n_used_slots] slot numbers, ascending per q_blk                  */
+} dcp_export_t;
+
+/* Copies one of the plan's integer arrays (int32) to host memory for bit-exact checks.
+ * dst may be NULL to query the length.  n_out receives the array length. */
+dcp_status_t dcp_plan_export(const dcp_plan_t* plan, dcp_export_t which, int32_t* dst_host,
+                             int64_t capacity, int64_t* n_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * Tensor descriptor shared by the launching calls.  Unused members are NULL / 0. */
+typedef struct {
+  int32_t hq, hkv, d;      /* heads and head dim; hq % hkv == 0                                  */
+  int32_t dtype;           /* dcp_dtype_t of q,k,v,out,dout,dq,dk,dv and of partial outputs      */
+  int32_t impl;            /* dcp_impl_t                                                         */
+  float softmax_scale;     /* multiplies Q K^T; the paper's 1/sqrt(D) (Sec. 2.1) is the default  */
+                           /* the caller passes explicitly                                       */
+  const void* q;  int64_t q_stride_t, q_stride_h;      /* device                                 */
+  const void* k;  int64_t k_stride_t, k_stride_h;
+  const void* v;  int64_t v_stride_t, v_stride_h;
+  const int32_t* attn_ranges; /* device int32[T,4]; required iff a kept row is RANGES            */
+  /* forward outputs.  Without slots: out [T,Hq,D] (strides below), lse [Hq,T].                  */
+  /* With slots: out = o_part [n_slots, block_size, Hq, D] contiguous, lse = lse_part            */
+  /* [n_slots, Hq, block_size]; rows past the block's length are not written.                    */
+  void* out;      int64_t o_stride_t, o_stride_h;
+  float* lse;
+  /* backward: out/lse above are then INPUTS holding the final (merged) O and LSE in the packed  */
+  /* layout, even when the plan uses slots.                                                      */
+  const void* dout; int64_t do_stride_t, do_stride_h;
+  void* dq;       int64_t dq_stride_t, dq_stride_h;
+  void* dk;       int64_t dk_stride_t, dk_stride_h;
+  void* dv;       int64_t dv_stride_t, dv_stride_h;
+} dcp_tensors_t;
+
+/* Blockwise Attention, forward (Listing 1 line 5; Sec. 5 "Blockwise Attention"): for every listed
+ * computation block S = scale * Q_i K_j^T, mask, online softmax, acc += P V_j; rows of one output
+ * unit accumulate in the kernel; O = acc / l, LSE = m + ln l (natural log of the sum of exp of
+ * scaled scores).  A query row that sees no key gets O = 0, LSE = -inf.  Every row of every
+ * q_blk (no slots) or of every used slot is written, also when no entry lists it. */
+dcp_status_t dcp_block_attn_fwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* stream);
+
+/* Blockwise Reduction (Listing 1 line 6 "RescaleAndSum"; Sec. 5 "Blockwise Reduction"):
+ * LSE = ln sum_p exp(LSE_p), O = sum_p exp(LSE_p - LSE) O_p over the slots of each q_blk.
+ *   o_part   device [n_slots, block_size, Hq, D] of `dtype`;  lse_part device float [n_slots, Hq, block_size]
+ *   out      device [T,Hq,D] of `dtype` with the given strides; lse device float [Hq,T]
+ * q blocks without any slot get O = 0, LSE = -inf. */
+dcp_status_t dcp_merge_partials(dcp_plan_t* plan, const void* o_part, const float* lse_part,
+                                void* out, int64_t o_stride_t, int64_t o_stride_h, float* lse,
+                                int32_t hq, int32_t d, int32_t dtype, void* stream);
+
+/* Backward preprocess: delta[h,t] = sum_d dO[t,h,d] * O[t,h,d] from the final O.  Reads t->out,
+ * t->dout (hq, d, dtype, strides); writes delta device float [Hq,T]. */
+dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_tokens, float* delta, void* stream);
+
+/* Bytes of device workspace dcp_block_attn_bwd needs for this plan and shape. */
+size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype);
+
+/* Blockwise Attention, backward (the mirrored instruction stream of Sec. 5; gradients of blocks
+ * that share a Q or KV block are reduced, Sec. 7.5): with P = exp(scale*S - LSE) on listed visible
+ * pairs (recomputed, never stored), dV_j += P^T dO_i, dP = dO_i V_j^T, dS = P * (dP - delta_i),
+ * dQ_i += scale dS K_j, dK_j += scale dS^T Q_i, KV-head gradients summed over the query heads of
+ * the group.  Inputs q,k,v,out,lse,dout; outputs dq,dk,dv (every element written; blocks nothing
+ * lists get zeros).  LSE and O are the GLOBAL ones: for a device's share of a plan the gradients
+ * are that share's partial sums.  workspace: device, >= dcp_bwd_workspace_bytes, 256-byte aligned. */
+dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
+/* Gradient reduction across blocks (Sec. 5 "Blockwise Reduction" used on gradients, Sec. 7.5):
+ * dst[i] = sum_p parts[p][i], accumulated in fp32, stored as dst_dtype.
+ *   parts_dev   device array of n_parts device pointers... passed by value below as host array  */
+dcp_status_t dcp_sum_partials(const void* const* parts_host_array_of_device_ptrs, int32_t n_parts,
+                              int32_t parts_dtype, void* dst, int32_t dst_dtype, int64_t n_elems,
+                              void* stream);
+
+/* Last error message of the calling thread ("" if none). */
+const char* dcp_last_error(void);
+
+/* Library version string and the kernel tile sizes in use, for logs. */
+const char* dcp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DCP_H_ */

@@ -1,0 +1,68 @@
+"""ctypes loader for libdcp_attn.so.  There is no fallback: if the library is missing it is
+built once with hipcc; if that fails the import error propagates."""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdcp_attn.so")
+
+i32p = ctypes.POINTER(ctypes.c_int32)
+i64p = ctypes.POINTER(ctypes.c_int64)
+vp = ctypes.c_void_p
+
+
+class Tensors(ctypes.Structure):
+    """Mirror of dcp_tensors_t (include/dcp.h)."""
+    _fields_ = [
+        ("hq", ctypes.c_int32), ("hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("impl", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+        ("q", vp), ("q_stride_t", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("k", vp), ("k_stride_t", ctypes.c_int64), ("k_stride_h", ctypes.c_int64),
+        ("v", vp), ("v_stride_t", ctypes.c_int64), ("v_stride_h", ctypes.c_int64),
+        ("attn_ranges", vp),
+        ("out", vp), ("o_stride_t", ctypes.c_int64), ("o_stride_h", ctypes.c_int64),
+        ("lse", vp),
+        ("dout", vp), ("do_stride_t", ctypes.c_int64), ("do_stride_h", ctypes.c_int64),
+        ("dq", vp), ("dq_stride_t", ctypes.c_int64), ("dq_stride_h", ctypes.c_int64),
+        ("dk", vp), ("dk_stride_t", ctypes.c_int64), ("dk_stride_h", ctypes.c_int64),
+        ("dv", vp), ("dv_stride_t", ctypes.c_int64), ("dv_stride_h", ctypes.c_int64),
+    ]
+
+
+_SIGS = {
+    "dcp_build_block_table": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, i32p, ctypes.c_int64, i64p]),
+    "dcp_count_pairs": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, i64p]),
+    "dcp_plan_create": (ctypes.c_int, [ctypes.POINTER(vp), i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, ctypes.c_int32]),
+    "dcp_plan_destroy": (ctypes.c_int, [vp]),
+    "dcp_plan_export": (ctypes.c_int, [vp, ctypes.c_int, i32p, ctypes.c_int64, i64p]),
+    "dcp_block_attn_fwd": (ctypes.c_int, [vp, ctypes.POINTER(Tensors), vp]),
+    "dcp_merge_partials": (ctypes.c_int, [vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]),
+    "dcp_bwd_delta": (ctypes.c_int, [ctypes.POINTER(Tensors), ctypes.c_int64, vp, vp]),
+    "dcp_bwd_workspace_bytes": (ctypes.c_size_t, [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]),
+    "dcp_block_attn_bwd": (ctypes.c_int, [vp, ctypes.POINTER(Tensors), vp, ctypes.c_size_t, vp]),
+    "dcp_sum_partials": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int64, vp]),
+    "dcp_last_error": (ctypes.c_char_p, []),
+    "dcp_version": (ctypes.c_char_p, []),
+}
+
+_lib = None
+
+
+def load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build(verbose=False)
+    lib = ctypes.CDLL(LIB_PATH)
+    for name, (res, args) in _SIGS.items():
+        fn = getattr(lib, name)          # AttributeError if the symbol is not exported
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def exported_names():
+    return list(_SIGS)

@@ -1,0 +1,195 @@
+"""Thin Python binding of the C ABI in include/dcp.h: same names, argument marshalling only.
+Host-side calls take numpy int32 arrays; launching calls take torch tensors (device memory and
+the current HIP stream come from PyTorch) and run entirely in the library's kernels."""
+import ctypes
+
+import numpy as np
+
+from . import _lib
+from ._lib import Tensors
+
+DCP_OK = 0
+DCP_ERR_INVALID_ARG, DCP_ERR_BAD_CU_SEQLENS, DCP_ERR_BAD_TABLE = -1, -2, -3
+DCP_ERR_UNSUPPORTED, DCP_ERR_WORKSPACE, DCP_ERR_HIP = -4, -5, -6
+DCP_MASK_NONE, DCP_MASK_CAUSAL, DCP_MASK_RANGES, DCP_MASK_SKIP = 0, 1, 2, 3
+DCP_BF16, DCP_F32 = 0, 1
+DCP_IMPL_AUTO, DCP_IMPL_SCALAR, DCP_IMPL_MFMA = 0, 1, 2
+EXPORTS = dict(BLK_START=0, BLK_LEN=1, BLK_SEQ=2, FWD_PTR=3, FWD_IDX=4, BWDQ_PTR=5, BWDQ_IDX=6,
+               BWDKV_PTR=7, BWDKV_IDX=8, SLOT_QBLK=9, MERGE_PTR=10, MERGE_IDX=11)
+
+
+class DcpError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"dcp status {status}: {msg}")
+        self.status = status
+
+
+def _check(st):
+    if st != DCP_OK:
+        raise DcpError(st, _lib.load().dcp_last_error().decode())
+
+
+def _i32(a):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(_lib.i32p)
+
+
+def dcp_last_error():
+    return _lib.load().dcp_last_error().decode()
+
+
+def dcp_version():
+    return _lib.load().dcp_version().decode()
+
+
+def dcp_build_block_table(cu_seqlens, block_size, attn_ranges):
+    """-> int32[n, 3] table of (q_blk, kv_blk, mask_kind)."""
+    lib = _lib.load()
+    cu, cu_p = _i32(cu_seqlens)
+    rg, rg_p = _i32(attn_ranges)
+    n = ctypes.c_int64(0)
+    _check(lib.dcp_build_block_table(cu_p, len(cu) - 1, block_size, rg_p, None, 0, ctypes.byref(n)))
+    table = np.zeros((n.value, 3), dtype=np.int32)
+    _check(lib.dcp_build_block_table(cu_p, len(cu) - 1, block_size, rg_p, table.ctypes.data_as(_lib.i32p), n.value, ctypes.byref(n)))
+    return table
+
+
+def dcp_count_pairs(cu_seqlens, block_size, table, attn_ranges=None):
+    lib = _lib.load()
+    cu, cu_p = _i32(cu_seqlens)
+    tb, tb_p = _i32(np.asarray(table).reshape(-1, 3))
+    rg, rg_p = _i32(attn_ranges)
+    out = np.zeros(len(tb), dtype=np.int64)
+    _check(lib.dcp_count_pairs(cu_p, len(cu) - 1, block_size, tb_p, len(tb), rg_p, out.ctypes.data_as(_lib.i64p)))
+    return out
+
+
+class Plan:
+    """Owner of a dcp_plan_t*."""
+
+    def __init__(self, handle, n_slots, block_size, total_tokens):
+        self.handle, self.n_slots, self.block_size, self.total_tokens = handle, n_slots, block_size, total_tokens
+
+    def export(self, which):
+        return dcp_plan_export(self, which)
+
+    def destroy(self):
+        if self.handle:
+            dcp_plan_destroy(self)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def dcp_plan_create(cu_seqlens, block_size, table, out_slot=None, n_slots=0):
+    lib = _lib.load()
+    cu, cu_p = _i32(cu_seqlens)
+    tb = np.ascontiguousarray(np.asarray(table, dtype=np.int32).reshape(-1, 3))
+    sl, sl_p = _i32(out_slot)
+    h = ctypes.c_void_p()
+    _check(lib.dcp_plan_create(ctypes.byref(h), cu_p, len(cu) - 1, block_size, tb.ctypes.data_as(_lib.i32p), len(tb), sl_p, n_slots))
+    return Plan(h, n_slots if out_slot is not None else 0, block_size, int(cu[-1]) if len(cu) else 0)
+
+
+def dcp_plan_destroy(plan):
+    _check(_lib.load().dcp_plan_destroy(plan.handle))
+    plan.handle = None
+
+
+def dcp_plan_export(plan, which):
+    lib = _lib.load()
+    wid = EXPORTS[which] if isinstance(which, str) else int(which)
+    n = ctypes.c_int64(0)
+    _check(lib.dcp_plan_export(plan.handle, wid, None, 0, ctypes.byref(n)))
+    out = np.zeros(n.value, dtype=np.int32)
+    _check(lib.dcp_plan_export(plan.handle, wid, out.ctypes.data_as(_lib.i32p), n.value, ctypes.byref(n)))
+    return out
+
+
+# ------------------------------------------------------------------ launching calls (torch)
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return DCP_BF16
+    if t.dtype == torch.float32:
+        return DCP_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _set(ts, name, tensor):
+    if tensor is None:
+        return
+    assert tensor.is_cuda and tensor.stride(-1) == 1, f"{name}: device tensor with contiguous last dim required"
+    setattr(ts, name, tensor.data_ptr())
+    prefix = {"q": "q", "k": "k", "v": "v", "out": "o", "dout": "do", "dq": "dq", "dk": "dk", "dv": "dv"}[name]
+    setattr(ts, prefix + "_stride_t", tensor.stride(0))
+    setattr(ts, prefix + "_stride_h", tensor.stride(1))
+
+
+def _descr(q, k, v, softmax_scale, attn_ranges, impl):
+    ts = Tensors()
+    ts.hq, ts.hkv, ts.d = q.shape[1], k.shape[1], q.shape[2]
+    ts.dtype, ts.impl, ts.softmax_scale = _dtype_code(q), impl, softmax_scale
+    _set(ts, "q", q)
+    _set(ts, "k", k)
+    _set(ts, "v", v)
+    if attn_ranges is not None:
+        assert attn_ranges.is_cuda and attn_ranges.is_contiguous()
+        ts.attn_ranges = attn_ranges.data_ptr()
+    return ts
+
+
+def dcp_block_attn_fwd(plan, q, k, v, out, lse, softmax_scale, attn_ranges=None, impl=DCP_IMPL_AUTO):
+    """out/lse: packed [T,Hq,D] / [Hq,T], or the partial-slot buffers when the plan has slots."""
+    ts = _descr(q, k, v, softmax_scale, attn_ranges, impl)
+    if plan.n_slots or out.dim() == 4:
+        assert out.is_contiguous() and lse.is_contiguous()
+        ts.out = out.data_ptr()
+    else:
+        _set(ts, "out", out)
+    ts.lse = lse.data_ptr()
+    _check(_lib.load().dcp_block_attn_fwd(plan.handle, ctypes.byref(ts), _stream()))
+
+
+def dcp_merge_partials(plan, o_part, lse_part, out, lse):
+    _check(_lib.load().dcp_merge_partials(plan.handle, o_part.data_ptr(), lse_part.data_ptr(), out.data_ptr(),
+                                          out.stride(0), out.stride(1), lse.data_ptr(), out.shape[1], out.shape[2],
+                                          _dtype_code(out), _stream()))
+
+
+def dcp_bwd_delta(out, dout, delta):
+    ts = Tensors()
+    ts.hq, ts.hkv, ts.d, ts.dtype = out.shape[1], out.shape[1], out.shape[2], _dtype_code(out)
+    _set(ts, "out", out)
+    _set(ts, "dout", dout)
+    _check(_lib.load().dcp_bwd_delta(ctypes.byref(ts), out.shape[0], delta.data_ptr(), _stream()))
+
+
+def dcp_bwd_workspace_bytes(plan, hq, hkv, d, dtype_code):
+    return int(_lib.load().dcp_bwd_workspace_bytes(plan.handle, hq, hkv, d, dtype_code))
+
+
+def dcp_block_attn_bwd(plan, q, k, v, out, lse, dout, dq, dk, dv, softmax_scale, workspace, attn_ranges=None,
+                       impl=DCP_IMPL_AUTO):
+    ts = _descr(q, k, v, softmax_scale, attn_ranges, impl)
+    for name, t in (("out", out), ("dout", dout), ("dq", dq), ("dk", dk), ("dv", dv)):
+        _set(ts, name, t)
+    ts.lse = lse.data_ptr()
+    _check(_lib.load().dcp_block_attn_bwd(plan.handle, ctypes.byref(ts), workspace.data_ptr(),
+                                          workspace.numel() * workspace.element_size(), _stream()))
+
+
+def dcp_sum_partials(parts, dst):
+    arr = (ctypes.c_void_p * len(parts))(*[p.data_ptr() for p in parts])
+    _check(_lib.load().dcp_sum_partials(arr, len(parts), _dtype_code(parts[0]), dst.data_ptr(), _dtype_code(dst),
+                                        dst.numel(), _stream()))

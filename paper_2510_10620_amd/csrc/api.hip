@@ -1,0 +1,172 @@
+// Launching entry points of the C ABI: argument validation (host side, complete before any
+// launch), kernel-family selection, and the enqueue of the kernels on the caller's stream.
+#include <cmath>
+
+#include "kernels.h"
+
+using namespace dcp;
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static dcp_status_t check_shape(const dcp_tensors_t* t) {
+  if (!t) return fail(DCP_ERR_INVALID_ARG, "tensor descriptor is NULL");
+  if (t->hq <= 0 || t->hkv <= 0 || t->d <= 0) return fail(DCP_ERR_INVALID_ARG, "hq, hkv, d must be positive");
+  if (t->hq % t->hkv != 0) return fail(DCP_ERR_UNSUPPORTED, "hq must be a multiple of hkv");
+  if (t->dtype != DCP_BF16 && t->dtype != DCP_F32) return fail(DCP_ERR_UNSUPPORTED, "dtype must be DCP_BF16 or DCP_F32");
+  if (t->impl < DCP_IMPL_AUTO || t->impl > DCP_IMPL_MFMA) return fail(DCP_ERR_INVALID_ARG, "bad impl selector");
+  if (!(t->softmax_scale > 0.f) || !std::isfinite(t->softmax_scale)) return fail(DCP_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+  return DCP_OK;
+}
+
+static dcp_status_t check_tensor(const char* name, const void* p, int64_t st, int64_t sh, int32_t d) {
+  if (!p) return fail(DCP_ERR_INVALID_ARG, std::string(name) + " is NULL");
+  if (!aligned16(p)) return fail(DCP_ERR_INVALID_ARG, std::string(name) + " must be 16-byte aligned");
+  if (sh < d || st < d || sh % 8 || st % 8) return fail(DCP_ERR_INVALID_ARG, std::string(name) + ": strides must be >= d and multiples of 8 elements");
+  return DCP_OK;
+}
+
+// Chooses the kernel family; MFMA iff requested or (AUTO and covered).
+static dcp_status_t pick_impl(const dcp_tensors_t* t, bool* use_mfma) {
+  const bool m_ok = mfma_supports(t->dtype, t->d), s_ok = scalar_supports(t->d);
+  if (t->impl == DCP_IMPL_MFMA) {
+    if (!m_ok) return fail(DCP_ERR_UNSUPPORTED, "MFMA kernels cover bf16 with head_dim 128 only");
+    *use_mfma = true;
+  } else if (t->impl == DCP_IMPL_SCALAR) {
+    if (!s_ok) return fail(DCP_ERR_UNSUPPORTED, "scalar kernels cover head_dim 32, 64, 128");
+    *use_mfma = false;
+  } else {
+    if (!m_ok && !s_ok) return fail(DCP_ERR_UNSUPPORTED, "no kernel covers this dtype / head_dim");
+    *use_mfma = m_ok;
+  }
+  return DCP_OK;
+}
+
+static KTensors pack(const dcp_plan_t* plan, const dcp_tensors_t* t) {
+  KTensors k{};
+  k.q = t->q; k.k = t->k; k.v = t->v; k.dout = t->dout; k.out_in = t->out;
+  k.out = t->out; k.dq = t->dq; k.dk = t->dk; k.dv = t->dv;
+  k.lse = t->lse; k.delta = nullptr; k.ranges = t->attn_ranges;
+  k.q_st = t->q_stride_t; k.q_sh = t->q_stride_h; k.k_st = t->k_stride_t; k.k_sh = t->k_stride_h;
+  k.v_st = t->v_stride_t; k.v_sh = t->v_stride_h; k.o_st = t->o_stride_t; k.o_sh = t->o_stride_h;
+  k.do_st = t->do_stride_t; k.do_sh = t->do_stride_h; k.dq_st = t->dq_stride_t; k.dq_sh = t->dq_stride_h;
+  k.dk_st = t->dk_stride_t; k.dk_sh = t->dk_stride_h; k.dv_st = t->dv_stride_t; k.dv_sh = t->dv_stride_h;
+  k.total_tokens = plan->total_tokens;
+  k.hq = t->hq; k.hkv = t->hkv; k.d = t->d; k.block_size = plan->block_size;
+  k.scale = t->softmax_scale;
+  k.use_slots = plan->use_slots ? 1 : 0;
+  return k;
+}
+
+extern "C" dcp_status_t dcp_block_attn_fwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* stream) {
+  if (!plan) return fail(DCP_ERR_INVALID_ARG, "plan is NULL");
+  dcp_status_t st = check_shape(t);
+  if (st != DCP_OK) return st;
+  bool use_mfma = false;
+  if ((st = pick_impl(t, &use_mfma)) != DCP_OK) return st;
+  if (plan->total_tokens == 0) return DCP_OK;
+  if ((st = check_tensor("q", t->q, t->q_stride_t, t->q_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("k", t->k, t->k_stride_t, t->k_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("v", t->v, t->v_stride_t, t->v_stride_h, t->d)) != DCP_OK) return st;
+  if (!t->out || !aligned16(t->out)) return fail(DCP_ERR_INVALID_ARG, "out is NULL or not 16-byte aligned");
+  if (!t->lse) return fail(DCP_ERR_INVALID_ARG, "lse is NULL");
+  if (!plan->use_slots && (st = check_tensor("out", t->out, t->o_stride_t, t->o_stride_h, t->d)) != DCP_OK) return st;
+  if (plan->has_ranges && !t->attn_ranges) return fail(DCP_ERR_INVALID_ARG, "table has RANGES rows but attn_ranges is NULL");
+  hipStream_t s = (hipStream_t)stream;
+  DevGroup g;
+  if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g)) != DCP_OK) return st;
+  KTensors k = pack(plan, t);
+  return use_mfma ? mfma_fwd(g, k, s) : scalar_fwd(g, k, t->dtype, s);
+}
+
+extern "C" dcp_status_t dcp_merge_partials(dcp_plan_t* plan, const void* o_part, const float* lse_part, void* out,
+                                           int64_t o_stride_t, int64_t o_stride_h, float* lse, int32_t hq, int32_t d,
+                                           int32_t dtype, void* stream) {
+  if (!plan) return fail(DCP_ERR_INVALID_ARG, "plan is NULL");
+  if (!plan->use_slots) return fail(DCP_ERR_INVALID_ARG, "plan was created without output slots");
+  if (hq <= 0 || d <= 0 || d % 8) return fail(DCP_ERR_UNSUPPORTED, "merge needs hq > 0 and d a positive multiple of 8");
+  if (dtype != DCP_BF16 && dtype != DCP_F32) return fail(DCP_ERR_UNSUPPORTED, "dtype must be DCP_BF16 or DCP_F32");
+  if (plan->total_tokens == 0) return DCP_OK;
+  if (plan->n_slots > 0 && (!o_part || !lse_part || !aligned16(o_part))) return fail(DCP_ERR_INVALID_ARG, "o_part / lse_part NULL or misaligned");
+  dcp_status_t st = check_tensor("out", out, o_stride_t, o_stride_h, d);
+  if (st != DCP_OK) return st;
+  if (!lse) return fail(DCP_ERR_INVALID_ARG, "lse is NULL");
+  hipStream_t s = (hipStream_t)stream;
+  if ((st = plan->ensure_device(s)) != DCP_OK) return st;
+  return stream_merge(plan->d_merge_ptr, plan->d_merge_idx, plan->d_fwd.blk_start, plan->d_fwd.blk_len, plan->n_blocks,
+                      plan->block_size, o_part, lse_part, out, o_stride_t, o_stride_h, lse, plan->total_tokens, hq, d,
+                      dtype, s);
+}
+
+extern "C" dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_tokens, float* delta, void* stream) {
+  if (!t) return fail(DCP_ERR_INVALID_ARG, "tensor descriptor is NULL");
+  if (t->hq <= 0 || t->d <= 0 || t->d % 8 || t->d > 256 || (t->d & (t->d - 1))) return fail(DCP_ERR_UNSUPPORTED, "delta needs d a power of two in 8..256");
+  if (t->dtype != DCP_BF16 && t->dtype != DCP_F32) return fail(DCP_ERR_UNSUPPORTED, "dtype must be DCP_BF16 or DCP_F32");
+  if (total_tokens < 0) return fail(DCP_ERR_INVALID_ARG, "total_tokens < 0");
+  if (total_tokens == 0) return DCP_OK;
+  dcp_status_t st;
+  if ((st = check_tensor("out", t->out, t->o_stride_t, t->o_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("dout", t->dout, t->do_stride_t, t->do_stride_h, t->d)) != DCP_OK) return st;
+  if (!delta) return fail(DCP_ERR_INVALID_ARG, "delta is NULL");
+  return stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
+                      total_tokens, t->hq, t->d, t->dtype, (hipStream_t)stream);
+}
+
+extern "C" size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype) {
+  (void)hkv; (void)d; (void)dtype;
+  if (!plan || hq <= 0) return 0;
+  size_t n = (size_t)hq * (size_t)plan->total_tokens * sizeof(float);  // delta [Hq,T]
+  return (n + 255) & ~(size_t)255;
+}
+
+extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  if (!plan) return fail(DCP_ERR_INVALID_ARG, "plan is NULL");
+  dcp_status_t st = check_shape(t);
+  if (st != DCP_OK) return st;
+  bool use_mfma = false;
+  if ((st = pick_impl(t, &use_mfma)) != DCP_OK) return st;
+  if (plan->total_tokens == 0) return DCP_OK;
+  if ((st = check_tensor("q", t->q, t->q_stride_t, t->q_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("k", t->k, t->k_stride_t, t->k_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("v", t->v, t->v_stride_t, t->v_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("out", t->out, t->o_stride_t, t->o_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("dout", t->dout, t->do_stride_t, t->do_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("dq", t->dq, t->dq_stride_t, t->dq_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("dk", t->dk, t->dk_stride_t, t->dk_stride_h, t->d)) != DCP_OK) return st;
+  if ((st = check_tensor("dv", t->dv, t->dv_stride_t, t->dv_stride_h, t->d)) != DCP_OK) return st;
+  if (!t->lse) return fail(DCP_ERR_INVALID_ARG, "lse is NULL");
+  if (plan->has_ranges && !t->attn_ranges) return fail(DCP_ERR_INVALID_ARG, "table has RANGES rows but attn_ranges is NULL");
+  const size_t need = dcp_bwd_workspace_bytes(plan, t->hq, t->hkv, t->d, t->dtype);
+  if (!workspace || workspace_bytes < need) return fail(DCP_ERR_WORKSPACE, "workspace is NULL or smaller than dcp_bwd_workspace_bytes");
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(DCP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  DevGroup gq, gkv;
+  if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &gq)) != DCP_OK) return st;
+  if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv)) != DCP_OK) return st;
+  KTensors k = pack(plan, t);
+  float* delta = (float*)workspace;
+  k.delta = delta;
+  if ((st = stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
+                         plan->total_tokens, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;
+  if (use_mfma) {
+    if ((st = mfma_bwd_dq(gq, k, s)) != DCP_OK) return st;
+    return mfma_bwd_dkv(gkv, k, s);
+  }
+  if ((st = scalar_bwd_dq(gq, k, t->dtype, s)) != DCP_OK) return st;
+  return scalar_bwd_dkv(gkv, k, t->dtype, s);
+}
+
+extern "C" dcp_status_t dcp_sum_partials(const void* const* parts, int32_t n_parts, int32_t parts_dtype, void* dst,
+                                         int32_t dst_dtype, int64_t n_elems, void* stream) {
+  if (n_parts < 1 || n_parts > 8 || !parts) return fail(DCP_ERR_INVALID_ARG, "n_parts must be 1..8 and parts non-NULL");
+  if (n_elems < 0 || n_elems % 8) return fail(DCP_ERR_INVALID_ARG, "n_elems must be a non-negative multiple of 8");
+  if ((parts_dtype != DCP_BF16 && parts_dtype != DCP_F32) || (dst_dtype != DCP_BF16 && dst_dtype != DCP_F32))
+    return fail(DCP_ERR_UNSUPPORTED, "dtype must be DCP_BF16 or DCP_F32");
+  if (n_elems == 0) return DCP_OK;
+  if (!dst || !aligned16(dst)) return fail(DCP_ERR_INVALID_ARG, "dst is NULL or misaligned");
+  for (int i = 0; i < n_parts; i++)
+    if (!parts[i] || !aligned16(parts[i])) return fail(DCP_ERR_INVALID_ARG, "a partial pointer is NULL or misaligned");
+  return stream_sum(parts, n_parts, parts_dtype, dst, dst_dtype, n_elems, (hipStream_t)stream);
+}
+
+extern "C" const char* dcp_version(void) { return "dcp_attn 0.1 (gfx950)"; }

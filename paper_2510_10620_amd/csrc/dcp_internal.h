@@ -1,0 +1,80 @@
+// Internal declarations shared by the host-side plan code and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "dcp.h"
+
+namespace dcp {
+
+void set_error(const std::string& msg);
+dcp_status_t fail(dcp_status_t code, const std::string& msg);
+
+#define DCP_HIP_TRY(expr)                                                                     \
+  do {                                                                                        \
+    hipError_t e__ = (expr);                                                                  \
+    if (e__ != hipSuccess)                                                                    \
+      return ::dcp::fail(DCP_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e__));    \
+  } while (0)
+
+// One (unit, tile) piece of work: `unit` indexes a Group's units, `tile` is the tile number
+// inside the unit's own block (tile * tile_rows is the first row).
+struct WorkItem {
+  int32_t unit;
+  int32_t tile;
+};
+
+// Device view of a grouping of table rows by a unit (an output block / slot, or a KV block).
+// Entry arrays describe the OTHER block of each row (the KV block for query-side groups, the
+// Q block for the KV-side group): first packed token, length, mask kind.
+struct DevGroup {
+  const int32_t* unit_blk;   // [n_units] block that owns the unit's rows
+  const int32_t* unit_out;   // [n_units] output slot (or -1: write to the packed tensor)
+  const int32_t* ptr;        // [n_units + 1]
+  const int32_t* ent_start;  // [nnz]
+  const int32_t* ent_len;    // [nnz]
+  const int32_t* ent_kind;   // [nnz]
+  const int32_t* blk_start;  // [n_blocks]
+  const int32_t* blk_len;    // [n_blocks]
+  const WorkItem* items;     // [n_items] longest first
+  int32_t n_items;
+  int32_t n_units;
+};
+
+struct HostGroup {
+  std::vector<int32_t> unit_blk, unit_out, ptr, idx, ent_start, ent_len, ent_kind;
+};
+
+struct DevItems {
+  WorkItem* items = nullptr;
+  int32_t n_items = 0;
+};
+
+}  // namespace dcp
+
+struct dcp_plan {
+  int32_t n_seq = 0, block_size = 0, n_blocks = 0, n_slots = 0;
+  int64_t total_tokens = 0, n_kept = 0;
+  bool use_slots = false, has_ranges = false;
+  std::vector<int32_t> cu, blk_start, blk_len, blk_seq;
+  std::vector<int32_t> table;  // original rows [n,3]
+  std::vector<int32_t> slot_qblk, merge_ptr, merge_idx;
+  dcp::HostGroup fwd, bwdq, bwdkv;
+
+  // device mirrors (created lazily on the device that is current at first launch)
+  std::mutex mu;
+  int device = -1;
+  int32_t* dev_arena = nullptr;
+  dcp::DevGroup d_fwd{}, d_bwdq{}, d_bwdkv{};
+  const int32_t *d_merge_ptr = nullptr, *d_merge_idx = nullptr, *d_slot_qblk = nullptr;
+  std::map<std::pair<int, int>, dcp::DevItems> items;  // (group id, tile rows) -> work list
+
+  dcp_status_t ensure_device(hipStream_t stream);
+  // group id: 0 fwd, 1 bwdq, 2 bwdkv
+  dcp_status_t group_for(int group_id, int tile_rows, hipStream_t stream, dcp::DevGroup* out);
+};

@@ -1,0 +1,48 @@
+// Launcher declarations: one function per kernel family, defined in the .hip files.
+#pragma once
+#include "dcp_internal.h"
+
+namespace dcp {
+
+// Plain-old-data copy of the caller's tensor descriptor plus derived fields, passed by value.
+struct KTensors {
+  const void *q, *k, *v, *dout, *out_in;
+  void *out, *dq, *dk, *dv;
+  float* lse;              // forward: output; backward: input
+  const float* delta;      // backward input [Hq,T]
+  const int32_t* ranges;   // [T,4] or null
+  int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh, dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
+  int64_t total_tokens;
+  int32_t hq, hkv, d, block_size;
+  float scale;
+  int32_t use_slots;
+};
+
+// scalar fp32-ALU family (any dtype; D in {32, 64, 128})
+bool scalar_supports(int32_t d);
+int scalar_fwd_tile();
+int scalar_bwd_tile();
+dcp_status_t scalar_fwd(const DevGroup& g, const KTensors& t, int32_t dtype, hipStream_t s);
+dcp_status_t scalar_bwd_dq(const DevGroup& g, const KTensors& t, int32_t dtype, hipStream_t s);
+dcp_status_t scalar_bwd_dkv(const DevGroup& g, const KTensors& t, int32_t dtype, hipStream_t s);
+
+// bf16 MFMA family (D = 128)
+bool mfma_supports(int32_t dtype, int32_t d);
+int mfma_fwd_tile();
+int mfma_dq_tile();
+int mfma_dkv_tile();
+dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s);
+dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s);
+dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s);
+
+// streaming (HBM-bound) kernels
+dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, const int32_t* blk_start,
+                          const int32_t* blk_len, int32_t n_blocks, int32_t block_size, const void* o_part,
+                          const float* lse_part, void* out, int64_t o_st, int64_t o_sh, float* lse,
+                          int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s);
+dcp_status_t stream_delta(const void* o, int64_t o_st, int64_t o_sh, const void* dout, int64_t do_st, int64_t do_sh,
+                          float* delta, int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s);
+dcp_status_t stream_sum(const void* const* parts, int32_t n_parts, int32_t parts_dtype, void* dst, int32_t dst_dtype,
+                        int64_t n, hipStream_t s);
+
+}  // namespace dcp

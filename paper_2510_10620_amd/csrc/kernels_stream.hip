@@ -1,0 +1,187 @@
+// HBM-bound streaming kernels: the LSE-carrying merge of partial outputs ("RescaleAndSum",
+// Listing 1 line 6; the paper's Blockwise Reduction instruction), the backward preprocess
+// delta = rowsum(dO * O), and the plain gradient sum across blocks.  Each thread moves 16-byte
+// vectors; all arithmetic is fp32.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace dcp {
+
+template <typename T> struct Vec8;  // 8 elements of D per thread
+template <> struct Vec8<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float* f) {
+    const uint4 u = *(const uint4*)p;
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) { f[2 * i] = __uint_as_float(w[i] << 16); f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float* f) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+    *(uint4*)p = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+template <> struct Vec8<float> {
+  static __device__ __forceinline__ void load(const float* p, float* f) {
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float* f) {
+    *(float4*)p = make_float4(f[0], f[1], f[2], f[3]);
+    *(float4*)(p + 4) = make_float4(f[4], f[5], f[6], f[7]);
+  }
+};
+
+// grid (ceil(block_size / kMergeRows), n_blocks); a workgroup merges kMergeRows rows of one q block
+// for all heads.  A thread item = (row, head, 8-wide chunk of D).
+static constexpr int kMergeRows = 4;
+
+template <typename T>
+__global__ __launch_bounds__(256) void merge_kernel(const int32_t* __restrict__ merge_ptr, const int32_t* __restrict__ merge_idx,
+                                                    const int32_t* __restrict__ blk_start, const int32_t* __restrict__ blk_len,
+                                                    int32_t block_size, const T* __restrict__ o_part,
+                                                    const float* __restrict__ lse_part, T* __restrict__ out, int64_t o_st,
+                                                    int64_t o_sh, float* __restrict__ lse, int64_t total_tokens, int32_t hq,
+                                                    int32_t d) {
+  const int b = blockIdx.y;
+  const int len = blk_len[b];
+  const int row0 = blockIdx.x * kMergeRows;
+  if (row0 >= len) return;
+  const int p0 = merge_ptr[b], p1 = merge_ptr[b + 1];
+  const int chunks = d / 8;
+  const int n_items = min(kMergeRows, len - row0) * hq * chunks;
+  for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
+    const int c = it % chunks, h = (it / chunks) % hq, row = row0 + it / (chunks * hq);
+    float m = -INFINITY;
+    for (int p = p0; p < p1; p++) m = fmaxf(m, lse_part[((int64_t)merge_idx[p] * hq + h) * block_size + row]);
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float tot = 0.f;
+    if (m > -INFINITY) {
+      for (int p = p0; p < p1; p++) {
+        const int slot = merge_idx[p];
+        const float lp = lse_part[((int64_t)slot * hq + h) * block_size + row];
+        if (lp == -INFINITY) continue;  // weight 0: never touch the partial's values
+        const float wgt = expf(lp - m);
+        tot += wgt;
+        float f[8];
+        Vec8<T>::load(o_part + (((int64_t)slot * block_size + row) * hq + h) * d + c * 8, f);
+#pragma unroll
+        for (int i = 0; i < 8; i++) acc[i] = fmaf(wgt, f[i], acc[i]);
+      }
+      const float inv = 1.f / tot;
+#pragma unroll
+      for (int i = 0; i < 8; i++) acc[i] *= inv;
+    }
+    const int64_t tok = (int64_t)blk_start[b] + row;
+    Vec8<T>::store(out + tok * o_st + (int64_t)h * o_sh + c * 8, acc);
+    if (c == 0) lse[(int64_t)h * total_tokens + tok] = m > -INFINITY ? m + logf(tot) : -INFINITY;
+  }
+}
+
+dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, const int32_t* blk_start,
+                          const int32_t* blk_len, int32_t n_blocks, int32_t block_size, const void* o_part,
+                          const float* lse_part, void* out, int64_t o_st, int64_t o_sh, float* lse,
+                          int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s) {
+  if (n_blocks == 0) return DCP_OK;
+  dim3 grid((block_size + kMergeRows - 1) / kMergeRows, n_blocks), block(256);
+  if (dtype == DCP_BF16)
+    hipLaunchKernelGGL(merge_kernel<bf16_t>, grid, block, 0, s, merge_ptr, merge_idx, blk_start, blk_len, block_size,
+                       (const bf16_t*)o_part, lse_part, (bf16_t*)out, o_st, o_sh, lse, total_tokens, hq, d);
+  else
+    hipLaunchKernelGGL(merge_kernel<float>, grid, block, 0, s, merge_ptr, merge_idx, blk_start, blk_len, block_size,
+                       (const float*)o_part, lse_part, (float*)out, o_st, o_sh, lse, total_tokens, hq, d);
+  DCP_HIP_TRY(hipGetLastError());
+  return DCP_OK;
+}
+
+// delta[h, t] = sum_d dO[t,h,d] * O[t,h,d].  A workgroup covers kDeltaTok tokens x all heads; the
+// d/8 lanes of one (token, head) reduce with shuffles; results pass through LDS so that each head
+// row of delta is written in contiguous runs of kDeltaTok floats.
+static constexpr int kDeltaTok = 32;
+
+template <typename T>
+__global__ __launch_bounds__(256) void delta_kernel(const T* __restrict__ o, int64_t o_st, int64_t o_sh,
+                                                    const T* __restrict__ dout, int64_t do_st, int64_t do_sh,
+                                                    float* __restrict__ delta, int64_t total_tokens, int32_t hq,
+                                                    int32_t d) {
+  extern __shared__ float sm[];  // [hq][kDeltaTok + 1]
+  const int64_t t0 = (int64_t)blockIdx.x * kDeltaTok;
+  const int ntok = (int)min((int64_t)kDeltaTok, total_tokens - t0);
+  const int chunks = d / 8;  // power of two <= 32 (d in 32..256)
+  const int n_items = ntok * hq * chunks;
+  const int n_iter = (n_items + blockDim.x - 1) / blockDim.x;
+  for (int k = 0; k < n_iter; k++) {
+    const int it = k * blockDim.x + threadIdx.x;
+    float sum = 0.f;
+    const int c = it % chunks, h = (it / chunks) % hq, tl = it / (chunks * hq);
+    if (it < n_items) {
+      float a[8], b[8];
+      Vec8<T>::load(o + (t0 + tl) * o_st + (int64_t)h * o_sh + c * 8, a);
+      Vec8<T>::load(dout + (t0 + tl) * do_st + (int64_t)h * do_sh + c * 8, b);
+#pragma unroll
+      for (int i = 0; i < 8; i++) sum = fmaf(a[i], b[i], sum);
+    }
+    for (int off = chunks / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (it < n_items && c == 0) sm[h * (kDeltaTok + 1) + tl] = sum;
+  }
+  __syncthreads();
+  for (int it = threadIdx.x; it < hq * ntok; it += blockDim.x) {
+    const int h = it / ntok, tl = it % ntok;
+    delta[(int64_t)h * total_tokens + t0 + tl] = sm[h * (kDeltaTok + 1) + tl];
+  }
+}
+
+dcp_status_t stream_delta(const void* o, int64_t o_st, int64_t o_sh, const void* dout, int64_t do_st, int64_t do_sh,
+                          float* delta, int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s) {
+  if (total_tokens == 0) return DCP_OK;
+  dim3 grid((unsigned)((total_tokens + kDeltaTok - 1) / kDeltaTok)), block(256);
+  const size_t sm = (size_t)hq * (kDeltaTok + 1) * sizeof(float);
+  if (dtype == DCP_BF16)
+    hipLaunchKernelGGL(delta_kernel<bf16_t>, grid, block, sm, s, (const bf16_t*)o, o_st, o_sh, (const bf16_t*)dout,
+                       do_st, do_sh, delta, total_tokens, hq, d);
+  else
+    hipLaunchKernelGGL(delta_kernel<float>, grid, block, sm, s, (const float*)o, o_st, o_sh, (const float*)dout, do_st,
+                       do_sh, delta, total_tokens, hq, d);
+  DCP_HIP_TRY(hipGetLastError());
+  return DCP_OK;
+}
+
+struct PartPtrs {
+  const void* p[8];
+};
+
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void sum_kernel(PartPtrs parts, int32_t n_parts, TO* __restrict__ dst, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (int64_t)gridDim.x * blockDim.x) {
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int p = 0; p < n_parts; p++) {
+      float f[8];
+      Vec8<TI>::load((const TI*)parts.p[p] + i * 8, f);
+#pragma unroll
+      for (int k = 0; k < 8; k++) acc[k] += f[k];
+    }
+    Vec8<TO>::store(dst + i * 8, acc);
+  }
+}
+
+dcp_status_t stream_sum(const void* const* parts, int32_t n_parts, int32_t parts_dtype, void* dst, int32_t dst_dtype,
+                        int64_t n, hipStream_t s) {
+  if (n == 0) return DCP_OK;
+  PartPtrs pp{};
+  for (int i = 0; i < n_parts; i++) pp.p[i] = parts[i];
+  const int64_t n8 = n / 8;
+  dim3 grid((unsigned)std::min<int64_t>((n8 + 255) / 256, 256 * 16)), block(256);
+  if (parts_dtype == DCP_F32 && dst_dtype == DCP_BF16)
+    hipLaunchKernelGGL((sum_kernel<float, bf16_t>), grid, block, 0, s, pp, n_parts, (bf16_t*)dst, n8);
+  else if (parts_dtype == DCP_F32 && dst_dtype == DCP_F32)
+    hipLaunchKernelGGL((sum_kernel<float, float>), grid, block, 0, s, pp, n_parts, (float*)dst, n8);
+  else if (parts_dtype == DCP_BF16 && dst_dtype == DCP_BF16)
+    hipLaunchKernelGGL((sum_kernel<bf16_t, bf16_t>), grid, block, 0, s, pp, n_parts, (bf16_t*)dst, n8);
+  else
+    hipLaunchKernelGGL((sum_kernel<bf16_t, float>), grid, block, 0, s, pp, n_parts, (float*)dst, n8);
+  DCP_HIP_TRY(hipGetLastError());
+  return DCP_OK;
+}
+
+}  // namespace dcp

@@ -1,0 +1,393 @@
+// Host side of the library: block generation from range arrays, pair counting, plan creation
+// (validation, block token ranges, CSR groupings, longest-first work lists) and the lazy device
+// mirror of the plan's integer arrays.  Follows Sec. 4.1 (block generation) and Sec. 5 (block
+// tables, block buffers) of the DCP paper; integer-only, compared bit-exactly with the tests'
+// independent reference.
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <numeric>
+#include <set>
+
+#include "dcp_internal.h"
+
+namespace dcp {
+
+static thread_local std::string g_err;
+void set_error(const std::string& msg) { g_err = msg; }
+dcp_status_t fail(dcp_status_t code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+
+struct Partition {
+  std::vector<int32_t> first, start, len, seq;
+};
+
+static dcp_status_t make_partition(const int32_t* cu, int32_t n_seq, int32_t B, Partition* p) {
+  if (n_seq < 0 || (n_seq > 0 && !cu)) return fail(DCP_ERR_INVALID_ARG, "cu_seqlens is NULL or n_seq < 0");
+  if (B <= 0) return fail(DCP_ERR_INVALID_ARG, "block_size must be positive");
+  if (n_seq > 0 && cu[0] != 0) return fail(DCP_ERR_BAD_CU_SEQLENS, "cu_seqlens[0] must be 0");
+  p->first.assign(1, 0);
+  for (int32_t s = 0; s < n_seq; s++) {
+    if (cu[s + 1] <= cu[s]) return fail(DCP_ERR_BAD_CU_SEQLENS, "cu_seqlens must be strictly increasing");
+    int32_t L = cu[s + 1] - cu[s];
+    int32_t nb = (L + B - 1) / B;
+    for (int32_t i = 0; i < nb; i++) {
+      p->start.push_back(cu[s] + i * B);
+      p->len.push_back(std::min(B, L - i * B));
+      p->seq.push_back(s);
+    }
+    p->first.push_back(p->first.back() + nb);
+  }
+  return DCP_OK;
+}
+
+// number of keys of [c0, c1) inside the union of a row's two ranges
+static inline int64_t row_visible(const int32_t* r, int64_t c0, int64_t c1) {
+  auto clip = [&](int64_t lo, int64_t hi) { return std::max<int64_t>(0, std::min(hi, c1) - std::max(lo, c0)); };
+  int64_t a = clip(r[0], r[1]), b = clip(r[2], r[3]);
+  int64_t olo = std::max<int64_t>(r[0], r[2]), ohi = std::min<int64_t>(r[1], r[3]);
+  return a + b - clip(olo, ohi);
+}
+
+}  // namespace dcp
+
+using namespace dcp;
+
+extern "C" const char* dcp_last_error(void) { return g_err.c_str(); }
+
+extern "C" dcp_status_t dcp_build_block_table(const int32_t* cu, int32_t n_seq, int32_t B, const int32_t* ranges,
+                                              int32_t* table_out, int64_t capacity, int64_t* n_out) {
+  if (!n_out) return fail(DCP_ERR_INVALID_ARG, "n_entries_out is NULL");
+  Partition p;
+  dcp_status_t st = make_partition(cu, n_seq, B, &p);
+  if (st != DCP_OK) return st;
+  if (!ranges && n_seq > 0) return fail(DCP_ERR_INVALID_ARG, "attn_ranges is NULL");
+  int64_t n = 0;
+  for (int32_t s = 0; s < n_seq; s++) {
+    for (int32_t qb = p.first[s]; qb < p.first[s + 1]; qb++) {
+      int64_t q0 = p.start[qb], q1 = q0 + p.len[qb];
+      for (int32_t kb = p.first[s]; kb < p.first[s + 1]; kb++) {
+        int64_t c0 = p.start[kb], c1 = c0 + p.len[kb];
+        bool any = false, all = true, causal = true;
+        for (int64_t i = q0; i < q1; i++) {
+          const int32_t* r = ranges + 4 * i;
+          int64_t nvis = row_visible(r, c0, c1);
+          any |= nvis > 0;
+          all &= nvis == c1 - c0;
+          // the causal predicate on this tile shows keys [c0, min(i + 1, c1)); the row matches it
+          // iff it sees exactly that many keys, all of them inside that prefix
+          int64_t want = std::max<int64_t>(0, std::min(i + 1, c1) - c0);
+          causal &= (nvis == want) && (row_visible(r, c0, c0 + want) == want);
+        }
+        if (!any) continue;
+        int32_t kind = all ? DCP_MASK_NONE : (causal ? DCP_MASK_CAUSAL : DCP_MASK_RANGES);
+        if (table_out && n < capacity) {
+          table_out[3 * n + 0] = qb;
+          table_out[3 * n + 1] = kb;
+          table_out[3 * n + 2] = kind;
+        }
+        n++;
+      }
+    }
+  }
+  *n_out = n;
+  if (table_out && n > capacity) return fail(DCP_ERR_INVALID_ARG, "block table capacity too small");
+  return DCP_OK;
+}
+
+extern "C" dcp_status_t dcp_count_pairs(const int32_t* cu, int32_t n_seq, int32_t B, const int32_t* table,
+                                        int64_t n_entries, const int32_t* ranges, int64_t* pairs_out) {
+  Partition p;
+  dcp_status_t st = make_partition(cu, n_seq, B, &p);
+  if (st != DCP_OK) return st;
+  if (n_entries < 0 || (n_entries > 0 && (!table || !pairs_out))) return fail(DCP_ERR_INVALID_ARG, "bad table / output pointer");
+  const int32_t nb = (int32_t)p.start.size();
+  for (int64_t e = 0; e < n_entries; e++) {
+    int32_t qb = table[3 * e], kb = table[3 * e + 1], kind = table[3 * e + 2];
+    if (qb < 0 || qb >= nb || kb < 0 || kb >= nb) return fail(DCP_ERR_BAD_TABLE, "block id out of range");
+    int64_t q0 = p.start[qb], q1 = q0 + p.len[qb], c0 = p.start[kb], c1 = c0 + p.len[kb];
+    int64_t n = 0;
+    if (kind == DCP_MASK_NONE) {
+      n = (q1 - q0) * (c1 - c0);
+    } else if (kind == DCP_MASK_CAUSAL) {
+      for (int64_t i = q0; i < q1; i++) n += std::max<int64_t>(0, std::min(i + 1, c1) - c0);
+    } else if (kind == DCP_MASK_RANGES) {
+      if (!ranges) return fail(DCP_ERR_INVALID_ARG, "RANGES row without attn_ranges");
+      for (int64_t i = q0; i < q1; i++) n += row_visible(ranges + 4 * i, c0, c1);
+    } else if (kind != DCP_MASK_SKIP) {
+      return fail(DCP_ERR_BAD_TABLE, "bad mask_kind");
+    }
+    pairs_out[e] = n;
+  }
+  return DCP_OK;
+}
+
+// Groups kept rows by unit_of(row); inside a unit ascending by other(row), stable.
+template <class UnitOf, class OtherOf>
+static void build_group(const dcp_plan& pl, const std::vector<int64_t>& kept, int32_t n_units, UnitOf unit_of,
+                        OtherOf other_of, HostGroup* g) {
+  std::vector<int64_t> order(kept);
+  std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) {
+    int32_t ua = unit_of(a), ub = unit_of(b);
+    if (ua != ub) return ua < ub;
+    return other_of(a) < other_of(b);
+  });
+  g->ptr.assign(n_units + 1, 0);
+  for (int64_t e : order) g->ptr[unit_of(e) + 1]++;
+  for (int32_t u = 0; u < n_units; u++) g->ptr[u + 1] += g->ptr[u];
+  g->idx.clear();
+  g->ent_start.clear();
+  g->ent_len.clear();
+  g->ent_kind.clear();
+  for (int64_t e : order) {
+    int32_t ob = other_of(e);
+    g->idx.push_back((int32_t)e);
+    g->ent_start.push_back(pl.blk_start[ob]);
+    g->ent_len.push_back(pl.blk_len[ob]);
+    g->ent_kind.push_back(pl.table[3 * e + 2]);
+  }
+}
+
+extern "C" dcp_status_t dcp_plan_create(dcp_plan_t** out, const int32_t* cu, int32_t n_seq, int32_t B,
+                                        const int32_t* table, int64_t n_entries, const int32_t* out_slot,
+                                        int32_t n_slots) {
+  if (!out) return fail(DCP_ERR_INVALID_ARG, "plan output pointer is NULL");
+  *out = nullptr;
+  Partition p;
+  dcp_status_t st = make_partition(cu, n_seq, B, &p);
+  if (st != DCP_OK) return st;
+  if (n_entries < 0 || (n_entries > 0 && !table)) return fail(DCP_ERR_INVALID_ARG, "block table is NULL or n_entries < 0");
+  if (out_slot && n_slots < 0) return fail(DCP_ERR_INVALID_ARG, "n_slots < 0");
+  if (n_entries > INT32_MAX) return fail(DCP_ERR_INVALID_ARG, "too many table rows");
+
+  std::unique_ptr<dcp_plan> pl(new dcp_plan);
+  pl->n_seq = n_seq;
+  pl->block_size = B;
+  pl->n_blocks = (int32_t)p.start.size();
+  pl->total_tokens = n_seq > 0 ? cu[n_seq] : 0;
+  pl->cu.assign(cu, cu + (n_seq > 0 ? n_seq + 1 : 0));
+  pl->blk_start = p.start;
+  pl->blk_len = p.len;
+  pl->blk_seq = p.seq;
+  pl->table.assign(table, table + 3 * n_entries);
+  pl->use_slots = out_slot != nullptr;
+  pl->n_slots = out_slot ? n_slots : 0;
+  pl->slot_qblk.assign(pl->n_slots, -1);
+
+  std::vector<int64_t> kept;
+  std::set<std::pair<int32_t, int32_t>> seen;
+  for (int64_t e = 0; e < n_entries; e++) {
+    int32_t qb = table[3 * e], kb = table[3 * e + 1], kind = table[3 * e + 2];
+    if (kind < 0 || kind > 3) return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": bad mask_kind");
+    if (qb < 0 || qb >= pl->n_blocks || kb < 0 || kb >= pl->n_blocks)
+      return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": block id out of range");
+    if (p.seq[qb] != p.seq[kb])
+      return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": q_blk and kv_blk belong to different sequences");
+    if (out_slot && (out_slot[e] < 0 || out_slot[e] >= n_slots))
+      return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": output slot out of range");
+    if (kind == DCP_MASK_SKIP) continue;
+    if (!seen.insert({qb, kb}).second)
+      return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": duplicate (q_blk, kv_blk)");
+    if (out_slot) {
+      int32_t& sq = pl->slot_qblk[out_slot[e]];
+      if (sq >= 0 && sq != qb)
+        return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": output slot shared by two q_blks");
+      sq = qb;
+    }
+    if (kind == DCP_MASK_RANGES) pl->has_ranges = true;
+    kept.push_back(e);
+  }
+  pl->n_kept = (int64_t)kept.size();
+
+  auto qb_of = [&](int64_t e) { return table[3 * e]; };
+  auto kb_of = [&](int64_t e) { return table[3 * e + 1]; };
+  if (out_slot) {
+    build_group(*pl, kept, n_slots, [&](int64_t e) { return out_slot[e]; }, kb_of, &pl->fwd);
+    pl->fwd.unit_blk = pl->slot_qblk;
+    pl->fwd.unit_out.resize(n_slots);
+    std::iota(pl->fwd.unit_out.begin(), pl->fwd.unit_out.end(), 0);
+  } else {
+    build_group(*pl, kept, pl->n_blocks, qb_of, kb_of, &pl->fwd);
+    pl->fwd.unit_blk.resize(pl->n_blocks);
+    std::iota(pl->fwd.unit_blk.begin(), pl->fwd.unit_blk.end(), 0);
+    pl->fwd.unit_out.assign(pl->n_blocks, -1);
+  }
+  build_group(*pl, kept, pl->n_blocks, qb_of, kb_of, &pl->bwdq);
+  build_group(*pl, kept, pl->n_blocks, kb_of, qb_of, &pl->bwdkv);
+  for (HostGroup* g : {&pl->bwdq, &pl->bwdkv}) {
+    g->unit_blk.resize(pl->n_blocks);
+    std::iota(g->unit_blk.begin(), g->unit_blk.end(), 0);
+    g->unit_out.assign(pl->n_blocks, -1);
+  }
+  // merge lists: the used slots of every q_blk, ascending
+  pl->merge_ptr.assign(pl->n_blocks + 1, 0);
+  for (int32_t s = 0; s < pl->n_slots; s++)
+    if (pl->slot_qblk[s] >= 0) pl->merge_ptr[pl->slot_qblk[s] + 1]++;
+  for (int32_t b = 0; b < pl->n_blocks; b++) pl->merge_ptr[b + 1] += pl->merge_ptr[b];
+  pl->merge_idx.assign(pl->merge_ptr.back(), 0);
+  {
+    std::vector<int32_t> fill(pl->merge_ptr.begin(), pl->merge_ptr.end() - 1);
+    for (int32_t s = 0; s < pl->n_slots; s++)
+      if (pl->slot_qblk[s] >= 0) pl->merge_idx[fill[pl->slot_qblk[s]]++] = s;
+  }
+  *out = pl.release();
+  return DCP_OK;
+}
+
+extern "C" dcp_status_t dcp_plan_destroy(dcp_plan_t* plan) {
+  if (!plan) return DCP_OK;
+  if (plan->dev_arena || !plan->items.empty()) {
+    int cur = -1;
+    (void)hipGetDevice(&cur);
+    if (plan->device >= 0 && cur != plan->device) (void)hipSetDevice(plan->device);
+    if (plan->dev_arena) (void)hipFree(plan->dev_arena);
+    for (auto& kv : plan->items)
+      if (kv.second.items) (void)hipFree(kv.second.items);
+    if (plan->device >= 0 && cur >= 0 && cur != plan->device) (void)hipSetDevice(cur);
+  }
+  delete plan;
+  return DCP_OK;
+}
+
+extern "C" dcp_status_t dcp_plan_export(const dcp_plan_t* plan, dcp_export_t which, int32_t* dst, int64_t capacity,
+                                        int64_t* n_out) {
+  if (!plan || !n_out) return fail(DCP_ERR_INVALID_ARG, "plan or n_out is NULL");
+  const std::vector<int32_t>* v = nullptr;
+  switch (which) {
+    case DCP_EXPORT_BLK_START: v = &plan->blk_start; break;
+    case DCP_EXPORT_BLK_LEN: v = &plan->blk_len; break;
+    case DCP_EXPORT_BLK_SEQ: v = &plan->blk_seq; break;
+    case DCP_EXPORT_FWD_PTR: v = &plan->fwd.ptr; break;
+    case DCP_EXPORT_FWD_IDX: v = &plan->fwd.idx; break;
+    case DCP_EXPORT_BWDQ_PTR: v = &plan->bwdq.ptr; break;
+    case DCP_EXPORT_BWDQ_IDX: v = &plan->bwdq.idx; break;
+    case DCP_EXPORT_BWDKV_PTR: v = &plan->bwdkv.ptr; break;
+    case DCP_EXPORT_BWDKV_IDX: v = &plan->bwdkv.idx; break;
+    case DCP_EXPORT_SLOT_QBLK: v = &plan->slot_qblk; break;
+    case DCP_EXPORT_MERGE_PTR: v = &plan->merge_ptr; break;
+    case DCP_EXPORT_MERGE_IDX: v = &plan->merge_idx; break;
+    default: return fail(DCP_ERR_INVALID_ARG, "unknown export id");
+  }
+  *n_out = (int64_t)v->size();
+  if (dst) {
+    if (capacity < (int64_t)v->size()) return fail(DCP_ERR_INVALID_ARG, "export capacity too small");
+    if (!v->empty()) std::memcpy(dst, v->data(), v->size() * sizeof(int32_t));
+  }
+  return DCP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// device mirror
+dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
+  std::lock_guard<std::mutex> lock(mu);
+  int cur = 0;
+  DCP_HIP_TRY(hipGetDevice(&cur));
+  if (dev_arena) {
+    if (cur != device) return fail(DCP_ERR_INVALID_ARG, "plan was first used on another device");
+    return DCP_OK;
+  }
+  std::vector<int32_t> host;
+  auto put = [&](const std::vector<int32_t>& v) {
+    size_t off = host.size();
+    host.insert(host.end(), v.begin(), v.end());
+    while (host.size() % 4) host.push_back(0);
+    return off;
+  };
+  size_t o_bs = put(blk_start), o_bl = put(blk_len);
+  struct Off { size_t ub, uo, ptr, es, el, ek; } go[3];
+  HostGroup* gs[3] = {&fwd, &bwdq, &bwdkv};
+  for (int i = 0; i < 3; i++)
+    go[i] = {put(gs[i]->unit_blk), put(gs[i]->unit_out), put(gs[i]->ptr), put(gs[i]->ent_start), put(gs[i]->ent_len), put(gs[i]->ent_kind)};
+  size_t o_mp = put(merge_ptr), o_mi = put(merge_idx), o_sq = put(slot_qblk);
+  host.push_back(0);
+  DCP_HIP_TRY(hipMalloc((void**)&dev_arena, host.size() * sizeof(int32_t)));
+  hipError_t e = hipMemcpyAsync(dev_arena, host.data(), host.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // `host` dies at scope exit
+  if (e != hipSuccess) {
+    (void)hipFree(dev_arena);
+    dev_arena = nullptr;
+    return fail(DCP_ERR_HIP, std::string("plan upload: ") + hipGetErrorString(e));
+  }
+  device = cur;
+  DevGroup* ds[3] = {&d_fwd, &d_bwdq, &d_bwdkv};
+  for (int i = 0; i < 3; i++) {
+    ds[i]->unit_blk = dev_arena + go[i].ub;
+    ds[i]->unit_out = dev_arena + go[i].uo;
+    ds[i]->ptr = dev_arena + go[i].ptr;
+    ds[i]->ent_start = dev_arena + go[i].es;
+    ds[i]->ent_len = dev_arena + go[i].el;
+    ds[i]->ent_kind = dev_arena + go[i].ek;
+    ds[i]->blk_start = dev_arena + o_bs;
+    ds[i]->blk_len = dev_arena + o_bl;
+    ds[i]->items = nullptr;
+    ds[i]->n_items = 0;
+    ds[i]->n_units = (int32_t)gs[i]->unit_blk.size();
+  }
+  d_merge_ptr = dev_arena + o_mp;
+  d_merge_idx = dev_arena + o_mi;
+  d_slot_qblk = dev_arena + o_sq;
+  return DCP_OK;
+}
+
+// Estimated visible pairs between packed rows [r0, r1) and the block [c0, c1) under `kind`;
+// `rows_are_keys` flips the causal predicate (rows are keys j, columns are queries i).
+static int64_t tile_cost(int32_t kind, int64_t r0, int64_t r1, int64_t c0, int64_t c1, bool rows_are_keys) {
+  int64_t n = 0;
+  if (kind == DCP_MASK_NONE) return (r1 - r0) * (c1 - c0);
+  if (kind == DCP_MASK_CAUSAL) {
+    if (!rows_are_keys)
+      for (int64_t i = r0; i < r1; i++) n += std::max<int64_t>(0, std::min(i + 1, c1) - c0);
+    else
+      for (int64_t j = r0; j < r1; j++) n += std::max<int64_t>(0, c1 - std::max(j, c0));
+    return n;
+  }
+  return (r1 - r0) * (c1 - c0) / 2;  // RANGES: unknown without the arrays; half is the estimate
+}
+
+dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, DevGroup* out) {
+  dcp_status_t st = ensure_device(stream);
+  if (st != DCP_OK) return st;
+  std::lock_guard<std::mutex> lock(mu);
+  HostGroup* hg = gid == 0 ? &fwd : (gid == 1 ? &bwdq : &bwdkv);
+  DevGroup dg = gid == 0 ? d_fwd : (gid == 1 ? d_bwdq : d_bwdkv);
+  auto key = std::make_pair(gid, tile_rows);
+  auto it = items.find(key);
+  if (it == items.end()) {
+    struct Scored { WorkItem w; int64_t cost; };
+    std::vector<Scored> sc;
+    for (int32_t u = 0; u < (int32_t)hg->unit_blk.size(); u++) {
+      int32_t b = hg->unit_blk[u];
+      if (b < 0) continue;  // unused slot
+      int32_t nt = (blk_len[b] + tile_rows - 1) / tile_rows;
+      for (int32_t t = 0; t < nt; t++) {
+        int64_t r0 = blk_start[b] + (int64_t)t * tile_rows;
+        int64_t r1 = std::min<int64_t>(r0 + tile_rows, blk_start[b] + blk_len[b]);
+        int64_t cost = 0;
+        for (int32_t e = hg->ptr[u]; e < hg->ptr[u + 1]; e++)
+          cost += tile_cost(hg->ent_kind[e], r0, r1, hg->ent_start[e], hg->ent_start[e] + hg->ent_len[e], gid == 2);
+        sc.push_back({{u, t}, cost});
+      }
+    }
+    std::stable_sort(sc.begin(), sc.end(), [](const Scored& a, const Scored& b) { return a.cost > b.cost; });
+    std::vector<WorkItem> w(sc.size());
+    for (size_t i = 0; i < sc.size(); i++) w[i] = sc[i].w;
+    DevItems di;
+    di.n_items = (int32_t)w.size();
+    if (!w.empty()) {
+      DCP_HIP_TRY(hipMalloc((void**)&di.items, w.size() * sizeof(WorkItem)));
+      hipError_t e = hipMemcpyAsync(di.items, w.data(), w.size() * sizeof(WorkItem), hipMemcpyHostToDevice, stream);
+      if (e == hipSuccess) e = hipStreamSynchronize(stream);
+      if (e != hipSuccess) {
+        (void)hipFree(di.items);
+        return fail(DCP_ERR_HIP, std::string("work list upload: ") + hipGetErrorString(e));
+      }
+    }
+    it = items.emplace(key, di).first;
+  }
+  dg.items = it->second.items;
+  dg.n_items = it->second.n_items;
+  *out = dg;
+  return DCP_OK;
+}

@@ -1,0 +1,117 @@
+"""Shared helpers for the parity tests: run the HIP path through the Python binding of the C ABI
+and the oracle on the same seeded inputs."""
+import numpy as np
+
+from oracle import attention as OA
+from oracle import blocks as OB
+from oracle import masks as OM
+from paper_2510_10620_amd import workloads as W
+
+
+def oracle_table(w):
+    """Block table from the oracle's own block generation (dense mask formula)."""
+    if w.dense_causal_table:
+        return OB.dense_causal_table(w.cu_seqlens, w.block_size)
+    return OB.table_from_mask(lambda s, L, r0, r1: OM.dense_rows(w.mask, L, r0, r1), w.cu_seqlens, w.block_size)
+
+
+def to_torch(w, a, device="cuda"):
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(device)
+    return torch.from_numpy(a).to(device)
+
+
+def from_torch(x):
+    import torch
+    return x.detach().to(torch.float64).cpu().numpy()
+
+
+class GpuRun:
+    """Holds device tensors of one workload and runs forward / merge / backward via the C ABI."""
+
+    def __init__(self, w, tensors, table, out_slot=None, n_slots=0, impl=0):
+        import torch
+        import paper_2510_10620_amd as P
+        self.P, self.torch, self.w, self.impl = P, torch, w, impl
+        self.table = np.asarray(table, dtype=np.int32).reshape(-1, 3)
+        self.plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, self.table, out_slot, n_slots)
+        self.use_slots = out_slot is not None
+        self.n_slots = n_slots
+        self.q, self.k, self.v = (to_torch(w, tensors[n]) for n in ("q", "k", "v"))
+        self.dout = to_torch(w, tensors["dout"]) if "dout" in tensors else None
+        self.ranges = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+        T = w.total_tokens
+        self.out = torch.full((T, w.hq, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+        self.lse = torch.full((w.hq, T), float("nan"), dtype=torch.float32, device="cuda")
+
+    def forward(self):
+        P, torch, w = self.P, self.torch, self.w
+        if self.use_slots:
+            self.o_part = torch.full((self.n_slots, w.block_size, w.hq, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+            self.lse_part = torch.full((self.n_slots, w.hq, w.block_size), float("nan"), dtype=torch.float32, device="cuda")
+            P.dcp_block_attn_fwd(self.plan, self.q, self.k, self.v, self.o_part, self.lse_part, w.softmax_scale, self.ranges, self.impl)
+            P.dcp_merge_partials(self.plan, self.o_part, self.lse_part, self.out, self.lse)
+        else:
+            P.dcp_block_attn_fwd(self.plan, self.q, self.k, self.v, self.out, self.lse, w.softmax_scale, self.ranges, self.impl)
+        torch.cuda.synchronize()
+        return from_torch(self.out), from_torch(self.lse)
+
+    def backward(self, out=None, lse=None):
+        """Uses the forward's out/lse unless the global ones are passed (device tensors)."""
+        P, torch, w = self.P, self.torch, self.w
+        out = self.out if out is None else out
+        lse = self.lse if lse is None else lse
+        T = w.total_tokens
+        self.dq = torch.full((T, w.hq, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+        self.dk = torch.full((T, w.hkv, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+        self.dv = torch.full((T, w.hkv, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+        nbytes = P.dcp_bwd_workspace_bytes(self.plan, w.hq, w.hkv, w.d, P.DCP_BF16 if w.dtype == "bf16" else P.DCP_F32)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        P.dcp_block_attn_bwd(self.plan, self.q, self.k, self.v, out, lse, self.dout, self.dq, self.dk, self.dv,
+                             w.softmax_scale, ws, self.ranges, self.impl)
+        torch.cuda.synchronize()
+        return from_torch(self.dq), from_torch(self.dk), from_torch(self.dv)
+
+
+def oracle_full(w, tensors, table, select=None, lse=None, delta=None, bwd=True, seqs=None, heads=None):
+    """Oracle forward (+ backward) on the full tensors, or on q heads `heads` (a list that must
+    cover whole KV groups' worth of the heads it names: heads are given as (q_heads, kv_head))."""
+    q, k, v = (W.to_f64(w, tensors[n]) for n in ("q", "k", "v"))
+    do = W.to_f64(w, tensors["dout"]) if "dout" in tensors else None
+    if heads is not None:
+        qh, kvh = heads
+        q, k, v = q[:, qh], k[:, [kvh]], v[:, [kvh]]
+        do = do[:, qh] if do is not None else None
+        lse = lse[qh] if lse is not None else None
+        delta = delta[qh] if delta is not None else None
+    vis = OB.Visibility(w.cu_seqlens, w.block_size, table, w.ranges, select=select)
+    O, LSE = OA.attention_fwd(q, k, v, w.cu_seqlens, vis, w.softmax_scale, seqs=seqs)
+    res = dict(out=O, lse=LSE)
+    if bwd:
+        dq, dk, dv = OA.attention_bwd(q, k, v, do, w.cu_seqlens, vis, w.softmax_scale, lse=lse, delta=delta, seqs=seqs)
+        res.update(dq=dq, dk=dk, dv=dv)
+    return res
+
+
+def max_abs(a, b):
+    """Max abs difference where the reference b is finite or both are equal infinities; positions
+    where b is NaN (not computed by the oracle) are ignored."""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    same_inf = np.isinf(b) & (a == b)
+    cmp = ~np.isnan(b) & ~same_inf
+    if not cmp.any():
+        return 0.0
+    d = np.abs(a[cmp] - b[cmp])
+    return float(np.nan_to_num(d, nan=np.inf, posinf=np.inf).max())
+
+
+TOL = {"bf16": dict(o=2e-2, lse=1e-5), "f32": dict(o=1e-4, lse=1e-5)}
+
+
+def check(w, got, ref, names, label=""):
+    tol = TOL[w.dtype]
+    for n in names:
+        err = max_abs(got[n], ref[n])
+        lim = tol["lse"] if n == "lse" else tol["o"]
+        assert err <= lim, f"{label} {n}: max abs err {err:.3e} > {lim:.1e}"

@@ -1,0 +1,160 @@
+"""Host-side logic of the C-ABI library (no GPU needed): symbols, block generation, pair counts,
+plan groupings bit-exact against the oracle's integer reference, and every error path."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2510_10620_amd as P
+from oracle import blocks as OB
+from oracle import masks as OM
+from paper_2510_10620_amd import _lib
+from paper_2510_10620_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "dcp.h")) as f:
+        src = f.read()
+    declared = set(re.findall(r"\b(dcp_[a-z_]+)\s*\(", src))
+    lib = ctypes.CDLL(_lib.LIB_PATH)
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in dcp.h but not exported"
+    assert declared == set(_lib.exported_names())
+    assert P.dcp_version().startswith("dcp_attn")
+
+
+def _oracle_table(spec, cu, B):
+    return OB.table_from_mask(lambda s, L, r0, r1: OM.dense_rows(spec, L, r0, r1), cu, B)
+
+
+SPECS = [W.MaskSpec("causal"), W.MaskSpec("window", window=90), W.MaskSpec("lambda", window=70, sink=9),
+         W.MaskSpec("causal_blockwise", window=2, sink=1, mblock=24), W.MaskSpec("shared_question")]
+
+
+@pytest.mark.parametrize("spec", SPECS, ids=lambda s: s.kind)
+@pytest.mark.parametrize("B", [1, 16, 37])
+def test_block_table_bit_exact_vs_oracle(spec, B):
+    rng = np.random.default_rng(B)
+    lens = [int(x) for x in rng.integers(1, 40 if B == 1 else 300, size=5)]
+    cu = W.cu_from_lengths(lens)
+    ranges = W.attn_ranges(spec, cu)
+    got = P.dcp_build_block_table(cu, B, ranges)
+    ref = _oracle_table(spec, cu, B)
+    assert got.dtype == np.int32 and np.array_equal(got, ref)
+    pc = P.dcp_count_pairs(cu, B, got, ranges)
+    assert np.array_equal(pc, OB.Visibility(cu, B, ref, ranges).pair_counts())
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_block_table_full_size_configs(cfg):
+    w = W.make_workload(cfg)
+    got = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+    ref = _oracle_table(w.mask, w.cu_seqlens, w.block_size)
+    assert np.array_equal(got, ref)
+    part = OB.block_partition(w.cu_seqlens, w.block_size)
+    plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, got)
+    assert np.array_equal(plan.export("BLK_START"), part["blk_start"])
+    assert np.array_equal(plan.export("BLK_LEN"), part["blk_end"] - part["blk_start"])
+    # visible-pair totals from closed forms of the mask families
+    total = 0
+    for s in range(len(w.cu_seqlens) - 1):
+        L = int(w.cu_seqlens[s + 1] - w.cu_seqlens[s])
+        i = np.arange(L, dtype=np.int64)
+        if w.mask.kind == "causal":
+            total += int((i + 1).sum())
+        elif w.mask.kind == "window":
+            total += int(np.minimum(i + 1, w.mask.window).sum())
+        else:
+            total += int((np.minimum(i + 1, w.mask.window) + np.minimum(w.mask.sink, np.maximum(i - w.mask.window + 1, 0))).sum())
+    assert int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, got, w.ranges).sum()) == total
+
+
+def test_plan_groupings_bit_exact_vs_oracle():
+    rng = np.random.default_rng(7)
+    lens = [150, 64, 33, 200]
+    B = 32
+    cu = W.cu_from_lengths(lens)
+    spec = W.MaskSpec("lambda", window=60, sink=10)
+    table = _oracle_table(spec, cu, B)
+    table = table[rng.permutation(len(table))]            # arbitrary row order
+    table[::7, 2] = W.MASK_SKIP                            # some rows dropped
+    part = OB.block_partition(cu, B)
+    nb = len(part["blk_seq"])
+    plan = P.dcp_plan_create(cu, B, table)
+    assert np.array_equal(plan.export("BLK_SEQ"), part["blk_seq"])
+    for col, ptr_name, idx_name in ((0, "FWD_PTR", "FWD_IDX"), (0, "BWDQ_PTR", "BWDQ_IDX"), (1, "BWDKV_PTR", "BWDKV_IDX")):
+        ptr, idx = OB.group_entries(table, col, nb)
+        assert np.array_equal(plan.export(ptr_name), ptr), ptr_name
+        assert np.array_equal(plan.export(idx_name), idx), idx_name
+    # with output slots: forward units are the slots
+    keep = np.arange(len(table))
+    slot, n_slots, slot_q = W.deal_divisions(table[:, 0], 3, 99)
+    plan2 = P.dcp_plan_create(cu, B, table, slot, n_slots + 2)   # two slots nobody uses
+    ptr, idx = OB.group_entries(table, 0, n_slots + 2, group_of=slot)
+    assert np.array_equal(plan2.export("FWD_PTR"), ptr)
+    assert np.array_equal(plan2.export("FWD_IDX"), idx)
+    sq = np.full(n_slots + 2, -1, dtype=np.int64)
+    for e in keep:
+        if table[e, 2] != W.MASK_SKIP:
+            sq[slot[e]] = table[e, 0]
+    assert np.array_equal(plan2.export("SLOT_QBLK"), sq)
+    mptr, midx = plan2.export("MERGE_PTR"), plan2.export("MERGE_IDX")
+    for b in range(nb):
+        assert midx[mptr[b]:mptr[b + 1]].tolist() == [s for s in range(n_slots + 2) if sq[s] == b]
+    # bwd groupings ignore slots
+    ptr, idx = OB.group_entries(table, 1, nb)
+    assert np.array_equal(plan2.export("BWDKV_IDX"), idx)
+
+
+def _status(fn, *a, **k):
+    with pytest.raises(P.DcpError) as ei:
+        fn(*a, **k)
+    assert str(ei.value) and P.dcp_last_error()
+    return ei.value.status
+
+
+def test_error_paths():
+    cu = W.cu_from_lengths([10, 6])
+    ok = np.array([[0, 0, 1], [2, 2, 1]], dtype=np.int32)       # B=8: blocks 0,1 | 2
+    P.dcp_plan_create(cu, 8, ok)
+    P.dcp_plan_create(cu, 8, np.zeros((0, 3), np.int32))          # empty table is legal
+    assert _status(P.dcp_plan_create, np.array([1, 5], np.int32), 8, ok) == P.DCP_ERR_BAD_CU_SEQLENS
+    assert _status(P.dcp_plan_create, np.array([0, 5, 5], np.int32), 8, ok) == P.DCP_ERR_BAD_CU_SEQLENS
+    assert _status(P.dcp_plan_create, cu, 0, ok) == P.DCP_ERR_INVALID_ARG
+    assert _status(P.dcp_plan_create, cu, 8, np.array([[0, 3, 0]], np.int32)) == P.DCP_ERR_BAD_TABLE     # id out of range
+    assert _status(P.dcp_plan_create, cu, 8, np.array([[-1, 0, 0]], np.int32)) == P.DCP_ERR_BAD_TABLE
+    assert _status(P.dcp_plan_create, cu, 8, np.array([[0, 2, 0]], np.int32)) == P.DCP_ERR_BAD_TABLE     # two sequences
+    assert _status(P.dcp_plan_create, cu, 8, np.array([[0, 0, 4]], np.int32)) == P.DCP_ERR_BAD_TABLE     # bad kind
+    assert _status(P.dcp_plan_create, cu, 8, np.array([[1, 0, 0], [1, 0, 1]], np.int32)) == P.DCP_ERR_BAD_TABLE  # duplicate
+    P.dcp_plan_create(cu, 8, np.array([[1, 0, 0], [1, 0, 3]], np.int32))                                  # SKIP duplicate is ignored
+    two = np.array([[0, 0, 1], [1, 0, 0]], np.int32)
+    assert _status(P.dcp_plan_create, cu, 8, two, np.array([0, 0], np.int32), 1) == P.DCP_ERR_BAD_TABLE  # slot with two q_blks
+    assert _status(P.dcp_plan_create, cu, 8, two, np.array([0, 2], np.int32), 2) == P.DCP_ERR_BAD_TABLE  # slot out of range
+    assert _status(P.dcp_count_pairs, cu, 8, np.array([[0, 0, 2]], np.int32), None) == P.DCP_ERR_INVALID_ARG
+    lib = _lib.load()
+    n = ctypes.c_int64()
+    rg = W.attn_ranges(W.MaskSpec("causal"), cu)
+    small = np.zeros((1, 3), np.int32)
+    st = lib.dcp_build_block_table(cu.ctypes.data_as(_lib.i32p), 2, 8, rg.ctypes.data_as(_lib.i32p),
+                                   small.ctypes.data_as(_lib.i32p), 1, ctypes.byref(n))
+    assert st == P.DCP_ERR_INVALID_ARG and n.value == 4
+    assert lib.dcp_plan_destroy(None) == 0
+
+
+def test_share_dealing_is_a_partition_with_valid_slots():
+    w = W.make_workload(5)
+    table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+    n_shares, share_seed, n_div, div_seed = w.share
+    sels = [W.deal_share(len(table), n_shares, share_seed, s) for s in range(n_shares)]
+    assert sorted(np.concatenate(sels).tolist()) == list(range(len(table)))
+    sub = table[sels[0]]
+    slot, n_slots, slot_q = W.deal_divisions(sub[:, 0], n_div, div_seed)
+    plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, sub, slot, n_slots)
+    assert np.array_equal(plan.export("SLOT_QBLK"), slot_q)
+    mptr = plan.export("MERGE_PTR")
+    assert (np.diff(mptr) <= n_div).all() and mptr[-1] == n_slots
