@@ -1,10 +1,300 @@
-#include "kernels.h"
+// Blockwise attention forward on bf16 MFMA (Listing 1 line 5 + the in-kernel part of line 6).
+//
+// One workgroup (4 waves) owns a query tile of 4 * 32 * NQ rows of one head and walks the KV tiles
+// (64 keys) of every table row of its output unit.  Scores are computed transposed,
+// S^T = K Q^T, so that a lane owns one query column: the running max / sum are per-lane scalars,
+// the only cross-lane step is one exchange between the two wave halves per 32 keys, and P^T in the
+// MFMA accumulator layout is directly the B operand of O^T += V^T P^T.  K and V tiles are copied
+// global -> LDS asynchronously one tile ahead into the other of two buffers; V^T fragments come
+// from transposing LDS reads.
+#include "mfma_common.h"
+
 namespace dcp {
-bool mfma_supports(int32_t, int32_t) { return false; }
-int mfma_fwd_tile() { return 128; }
-int mfma_dq_tile() { return 128; }
-int mfma_dkv_tile() { return 128; }
-dcp_status_t mfma_fwd(const DevGroup&, const KTensors&, hipStream_t) { return fail(DCP_ERR_UNSUPPORTED, "stub"); }
-dcp_status_t mfma_bwd_dq(const DevGroup&, const KTensors&, hipStream_t) { return fail(DCP_ERR_UNSUPPORTED, "stub"); }
-dcp_status_t mfma_bwd_dkv(const DevGroup&, const KTensors&, hipStream_t) { return fail(DCP_ERR_UNSUPPORTED, "stub"); }
+
+template <int NQ>
+struct FwdCfg {
+  static constexpr int kWaveRows = 32 * NQ;
+  static constexpr int kTileM = 4 * kWaveRows;
+};
+
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Walks the (table row, key tile) pairs of a unit that the workgroup cannot skip.  All state is
+// wave-uniform.
+struct KvIter {
+  const int32_t *ent_start, *ent_len, *ent_kind;
+  int e, e_end, jt, n_t;
+  int c0, c1, kind;
+  int ks;  // first key of the current tile
+  __device__ KvIter(const DevGroup& g, int unit) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind) {
+    e = g.ptr[unit] - 1; e_end = g.ptr[unit + 1]; jt = 0; n_t = 0; c0 = c1 = kind = 0; ks = 0;
+  }
+  // Advances to the next tile some row of [.., q_hi] may see; false when the unit is done.
+  __device__ bool next(int q_hi, const RangeBounds& rb) {
+    for (;;) {
+      jt++;
+      if (jt >= n_t) {
+        e++;
+        if (e >= e_end) return false;
+        c0 = ent_start[e]; c1 = c0 + ent_len[e]; kind = ent_kind[e];
+        n_t = (c1 - c0 + kTN - 1) / kTN;
+        if (kind == 1) n_t = min(n_t, max(0, (q_hi - c0) / kTN + 1));  // tiles starting after q_hi are empty
+        jt = -1;
+        continue;
+      }
+      ks = c0 + jt * kTN;
+      if (kind != 2 || rb.may_see(ks, min(ks + kTN, c1))) return true;
+    }
+  }
+};
+
+// Class of the 32-key sub-tile [ks, ks + 32) for the rows [q_lo, q_hi] with bounds rb.
+__device__ __forceinline__ int classify32(int kind, int ks, int c1, int q_lo, int q_hi, const RangeBounds& rb) {
+  if (ks >= c1) return kSkip;
+  const int ke = min(ks + 32, c1);
+  const bool whole = ks + 32 <= c1;
+  if (kind == 0) return whole ? kFull : kPartial;
+  if (kind == 1) {
+    if (ks > q_hi) return kSkip;
+    return (whole && ke - 1 <= q_lo) ? kFull : kPartial;
+  }
+  if (!rb.may_see(ks, ke)) return kSkip;
+  return (whole && rb.all_see(ks, ke)) ? kFull : kPartial;
 }
+
+template <int NQ>
+struct FwdState {
+  bf16x8 qf[NQ][8];
+  f32x16 o[NQ][4];
+  float m[NQ], l[NQ];
+  int qi[NQ];
+  int4 qr[NQ];
+  FragAddr fa;
+};
+
+// One 32-key sub-tile: S^T = K Q^T, mask, online softmax, O^T += V^T P^T.
+template <int NQ, bool MASK>
+__device__ __forceinline__ void fwd_subtile(FwdState<NQ>& st, const char* k_lds, const char* v_lds, int kt, int ks32,
+                                            int kind, int c0, int c1, float c_log2, int lane) {
+  const int lh = lane >> 5;
+  f32x16 s[NQ];
+#pragma unroll
+  for (int nq = 0; nq < NQ; nq++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) s[nq][r] = 0.f;
+#pragma unroll
+  for (int ksd = 0; ksd < 8; ksd++) {
+    const bf16x8 a = frag_rm(k_lds, st.fa, 32 * kt, ksd);
+#pragma unroll
+    for (int nq = 0; nq < NQ; nq++) s[nq] = mfma(a, st.qf[nq][ksd], s[nq]);
+  }
+  if (MASK) {
+#pragma unroll
+    for (int nq = 0; nq < NQ; nq++) {
+      const RowRanges rr = row_ranges(kind, st.qi[nq], c0, c1, st.qr[nq]);
+      const int kb = ks32 + 4 * lh;
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int key = kb + 8 * (r / 4) + (r % 4);
+        if (!rr.sees(key)) s[nq][r] = -INFINITY;
+      }
+    }
+  }
+  bf16x8 p[NQ][2];
+#pragma unroll
+  for (int nq = 0; nq < NQ; nq++) {
+    float mx = s[nq][0];
+#pragma unroll
+    for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[nq][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(st.m[nq], mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f((st.m[nq] - m_use) * c_log2);
+    const float mc = m_use * c_log2;
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const float e = __builtin_amdgcn_exp2f(fmaf(s[nq][r], c_log2, -mc));
+      s[nq][r] = e;
+      sum += e;
+    }
+    st.l[nq] = st.l[nq] * alpha + sum;
+    st.m[nq] = m_new;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) st.o[nq][dt][r] *= alpha;
+    }
+#pragma unroll
+    for (int c = 0; c < 2; c++) p[nq][c] = pack_frag(s[nq], c);
+  }
+#pragma unroll
+  for (int c = 0; c < 2; c++)
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) {
+      const bf16x8 a = frag_tr(v_lds, st.fa, 32 * kt + 16 * c, dt);
+#pragma unroll
+      for (int nq = 0; nq < NQ; nq++) st.o[nq][dt] = mfma(a, p[nq][c], st.o[nq][dt]);
+    }
+}
+
+template <int NQ>
+__global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGroup g, KTensors t) {
+  constexpr int WR = FwdCfg<NQ>::kWaveRows, TM = FwdCfg<NQ>::kTileM;
+  // two stages, each [K tile | V tile]; separate arrays so that the asynchronous copy into one is
+  // known not to alias the reads from the other
+  __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
+  __shared__ int wg_bounds[4][8];
+
+  int item, head;
+  const int G = t.hq / t.hkv;
+  if (!decode_wg(g.n_items, t.hkv, G, &item, &head)) return;
+  const int hk = head / G;
+  const WorkItem w = g.items[item];
+  const int qb = g.unit_blk[w.unit];
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int li = lane & 31, lh = lane >> 5;
+  const int blk_start = g.blk_start[qb], blk_len = g.blk_len[qb];
+  const int row0 = w.tile * TM;                       // first row of the tile inside the block
+  const int n_rows = min(TM, blk_len - row0);         // valid rows of the tile (>= 1)
+  const int q_lo = blk_start + row0, q_hi = q_lo + n_rows - 1;
+  const int wrow0 = wave * WR;                        // wave's first row inside the tile
+  const int w_rows = max(0, min(WR, n_rows - wrow0)); // wave's valid rows
+  const int wq_lo = q_lo + wrow0, wq_hi = wq_lo + w_rows - 1;
+
+  FwdState<NQ> st;
+  st.fa.init(lane);
+  bool qv[NQ];
+  RangeBounds wrb;
+  wrb.init();
+#pragma unroll
+  for (int nq = 0; nq < NQ; nq++) {
+    const int r = wrow0 + nq * 32 + li;
+    qv[nq] = r < n_rows;
+    st.qi[nq] = q_lo + min(r, n_rows - 1);
+    st.qr[nq] = make_int4(0, 0, 0, 0);
+    if (t.ranges) {
+      st.qr[nq] = ((const int4*)t.ranges)[st.qi[nq]];
+      if (qv[nq]) wrb.add(st.qr[nq]);
+    }
+  }
+  RangeBounds rb = wrb;  // workgroup bounds
+  if (t.ranges) {
+    wrb.wave_reduce();
+    if (lane == 0) {
+      wg_bounds[wave][0] = wrb.lo_min[0]; wg_bounds[wave][1] = wrb.lo_max[0]; wg_bounds[wave][2] = wrb.hi_min[0]; wg_bounds[wave][3] = wrb.hi_max[0];
+      wg_bounds[wave][4] = wrb.lo_min[1]; wg_bounds[wave][5] = wrb.lo_max[1]; wg_bounds[wave][6] = wrb.hi_min[1]; wg_bounds[wave][7] = wrb.hi_max[1];
+    }
+    __syncthreads();
+    rb.init();
+    for (int x = 0; x < 4; x++) {
+      rb.lo_min[0] = min(rb.lo_min[0], wg_bounds[x][0]); rb.lo_max[0] = max(rb.lo_max[0], wg_bounds[x][1]);
+      rb.hi_min[0] = min(rb.hi_min[0], wg_bounds[x][2]); rb.hi_max[0] = max(rb.hi_max[0], wg_bounds[x][3]);
+      rb.lo_min[1] = min(rb.lo_min[1], wg_bounds[x][4]); rb.lo_max[1] = max(rb.lo_max[1], wg_bounds[x][5]);
+      rb.hi_min[1] = min(rb.hi_min[1], wg_bounds[x][6]); rb.hi_max[1] = max(rb.hi_max[1], wg_bounds[x][7]);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+      rb.lo_min[k] = uni(rb.lo_min[k]); rb.lo_max[k] = uni(rb.lo_max[k]); rb.hi_min[k] = uni(rb.hi_min[k]); rb.hi_max[k] = uni(rb.hi_max[k]);
+      wrb.lo_min[k] = uni(wrb.lo_min[k]); wrb.lo_max[k] = uni(wrb.lo_max[k]); wrb.hi_min[k] = uni(wrb.hi_min[k]); wrb.hi_max[k] = uni(wrb.hi_max[k]);
+    }
+  }
+
+  // Q fragments (B operand: lane = query column li, d = 16 ks + 8 lh ..)
+#pragma unroll
+  for (int nq = 0; nq < NQ; nq++) {
+    const bf16_t* qp = (const bf16_t*)t.q + (int64_t)st.qi[nq] * t.q_st + (int64_t)head * t.q_sh + 8 * lh;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) st.qf[nq][ks] = as_frag(*(const uint4*)(qp + 16 * ks));
+    st.m[nq] = -INFINITY; st.l[nq] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) st.o[nq][dt][r] = 0.f;
+  }
+  const float c_log2 = t.scale * 1.44269504088896340736f;
+  const bf16_t* kbase = (const bf16_t*)t.k + (int64_t)hk * t.k_sh;
+  const bf16_t* vbase = (const bf16_t*)t.v + (int64_t)hk * t.v_sh;
+
+  KvIter it(g, w.unit);
+  bool have = it.next(q_hi, rb);
+  if (have) {
+    tile_load_async(stage0, kbase, t.k_st, it.ks, it.c1 - 1, wave, lane);
+    tile_load_async(stage0 + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave, lane);
+  }
+  __syncthreads();
+
+  // one pipeline step: prefetch the next tile into `nxt`, compute the current one from `cur`
+  auto step = [&](const char* cur, char* nxt) {
+    const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
+    have = it.next(q_hi, rb);
+    if (have) {
+      tile_load_async(nxt, kbase, t.k_st, it.ks, it.c1 - 1, wave, lane);
+      tile_load_async(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave, lane);
+    }
+    if (w_rows > 0) {
+#pragma unroll
+      for (int kt = 0; kt < 2; kt++) {
+        const int cls = classify32(kind, ks + 32 * kt, c1, wq_lo, wq_hi, wrb);
+        if (cls == kFull)
+          fwd_subtile<NQ, false>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane);
+        else if (cls == kPartial)
+          fwd_subtile<NQ, true>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane);
+      }
+    }
+    __syncthreads();  // the copy into `nxt` has landed (vmcnt) and `cur` may be overwritten
+  };
+  while (have) {
+    step(stage0, stage1);
+    if (!have) break;
+    step(stage1, stage0);
+  }
+
+  // ---- epilogue: O = acc / l, LSE = ln2 * (m c + log2 l)
+  const int slot = g.unit_out[w.unit];
+#pragma unroll
+  for (int nq = 0; nq < NQ; nq++) {
+    const float lt = st.l[nq] + __shfl_xor(st.l[nq], 32);
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+    const float lse = lt > 0.f ? (st.m[nq] * c_log2 + __builtin_amdgcn_logf(lt)) * 0.69314718055994530942f : -INFINITY;
+    if (!qv[nq]) continue;
+    const int row = row0 + wrow0 + nq * 32 + li;  // row inside the block
+    bf16_t* op;
+    if (slot < 0) {
+      op = (bf16_t*)t.out + (int64_t)(blk_start + row) * t.o_st + (int64_t)head * t.o_sh;
+      if (lh == 0) t.lse[(int64_t)head * t.total_tokens + blk_start + row] = lse;
+    } else {
+      op = (bf16_t*)t.out + (((int64_t)slot * t.block_size + row) * t.hq + head) * kD;
+      if (lh == 0) t.lse[((int64_t)slot * t.hq + head) * t.block_size + row] = lse;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int a = 0; a < 4; a++) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(st.o[nq][dt][4 * a] * inv) | ((uint32_t)f32_to_bf16(st.o[nq][dt][4 * a + 1] * inv) << 16);
+        pk.y = (uint32_t)f32_to_bf16(st.o[nq][dt][4 * a + 2] * inv) | ((uint32_t)f32_to_bf16(st.o[nq][dt][4 * a + 3] * inv) << 16);
+        *(uint2*)(op + 32 * dt + 8 * a + 4 * lh) = pk;
+      }
+  }
+}
+
+bool mfma_supports(int32_t dtype, int32_t d) { return dtype == DCP_BF16 && d == kD; }
+
+#ifndef DCP_FWD_NQ
+#define DCP_FWD_NQ 1
+#endif
+int mfma_fwd_tile() { return FwdCfg<DCP_FWD_NQ>::kTileM; }
+
+dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s) {
+  if (g.n_items == 0) return DCP_OK;
+  const int total = g.n_items * t.hq;
+  const int per_xcd = (total + 7) / 8;
+  hipLaunchKernelGGL(mfma_fwd_kernel<DCP_FWD_NQ>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  DCP_HIP_TRY(hipGetLastError());
+  return DCP_OK;
+}
+
+}  // namespace dcp

@@ -1,0 +1,224 @@
+// Shared device code of the bf16 MFMA kernels (gfx950): fragment types, the LDS tile layout,
+// tile staging, per-row mask ranges and tile classification.
+//
+// MFMA used: v_mfma_f32_32x32x16_bf16.  Operand layouts (lane l, i = l % 32, h = l / 32):
+//   A (32 x 16): lane holds row i, k = 8h .. 8h+7          (8 bf16)
+//   B (16 x 32): lane holds column i, k = 8h .. 8h+7       (8 bf16)
+//   C (32 x 32): lane holds column i, register r holds row 8*(r/4) + 4h + (r%4)   (16 fp32)
+// Because the contraction index k may be permuted as long as A and B agree, registers
+// 8c .. 8c+7 of a C tile (rows 16c + 8a + 4h + b, a in {0,1}, b in 0..3) serve directly as the
+// B operand of a following MFMA whose A operand supplies k-slot 8h + 4a + b from row 16c+8a+4h+b.
+//
+// LDS tiles are [rows][128] bf16, 256 bytes per row, no padding; the 16-byte chunk c of a row is
+// stored at chunk c ^ swz(row).  With swz(row) = ((row & 3) << 2) | ((row >> 2) & 3) both access
+// patterns are bank-conflict free: 16 consecutive rows at one chunk (row-major ds_read_b128) land
+// in 16 different chunks, and 4 consecutive rows x 64 bytes (ds_read_b64_tr_b16 of a half-wave)
+// land in 4 different 64-byte groups.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+#include "device_utils.h"
+#include "dcp_internal.h"
+#include "kernels.h"
+
+namespace dcp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+static constexpr int kD = 128;        // head dim of the MFMA family
+static constexpr int kRowBytes = 256; // one tile row
+static constexpr int kTN = 64;        // rows of a streamed tile (keys in fwd/dQ, queries in dK/dV)
+static constexpr int kTileBytes = kTN * kRowBytes;
+
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+__device__ __forceinline__ int tile_off(int row, int c16) { return row * kRowBytes + ((c16 ^ swz(row)) << 4); }
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+
+// Row-major A/B fragment: 16 bytes of `row` at chunk c16.
+__device__ __forceinline__ bf16x8 lds_frag(const char* tile, int row, int c16) {
+  return as_frag(*(const uint4*)(tile + tile_off(row, c16)));
+}
+
+// Transposed fragment via two ds_read_b64_tr_b16: the lane receives, for tile column `col0 + l%32`
+// (l%32 = 16*(blk%2) + j), the 8 values of rows  row0 + 8a + 4h + b  (a = 0,1; b = 0..3) in k-slot
+// order 4a + b.  Inside a 16-lane block, lane j supplies the address of row (j / 4), columns
+// 4*(j % 4) .. +3 and receives column j of the 4 rows.
+__device__ __forceinline__ bf16x8 lds_frag_tr(const char* tile, int row0, int col0, int lane) {
+  const int j = lane & 15, blk = lane >> 4, h = blk >> 1;
+  const int col = col0 + 16 * (blk & 1) + 4 * (j & 3);
+  const int r0 = row0 + 4 * h + (j >> 2);
+  typedef __attribute__((address_space(3))) s16x4* lds_p;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(tile + tile_off(r0, col >> 3) + (col & 7) * 2));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(tile + tile_off(r0 + 8, col >> 3) + (col & 7) * 2));
+  s16x8 v;
+  v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3]; v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Lane-dependent parts of the fragment addresses, computed once.  Rows enter the swizzle only
+// through row % 16, so a fragment whose first row is a multiple of 16 (resp. 32) is reached from
+// these by adding a compile-time multiple of the row pitch, which folds into the LDS
+// instruction's immediate offset.
+struct FragAddr {
+  int rm[8];     // row-major fragment of row (l % 32), chunk 2 ks + (l / 32), ks = 0..7
+  int tr[4][2];  // transposed fragment for columns 32 dt .. 32 dt + 31: rows 4h + j/4 (+8)
+  __device__ __forceinline__ void init(int lane) {
+    const int li = lane & 31, lh = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) rm[ks] = tile_off(li, 2 * ks + lh);
+    const int j = lane & 15, blk = lane >> 4, h = blk >> 1;
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) {
+      const int col = 32 * dt + 16 * (blk & 1) + 4 * (j & 3);
+      const int r0 = 4 * h + (j >> 2);
+      tr[dt][0] = tile_off(r0, col >> 3) + (col & 7) * 2;
+      tr[dt][1] = tile_off(r0 + 8, col >> 3) + (col & 7) * 2;
+    }
+  }
+};
+
+// Row-major fragment of rows row0 .. row0+31 (row0 a multiple of 32), k-step ks.
+__device__ __forceinline__ bf16x8 frag_rm(const char* tile, const FragAddr& fa, int row0, int ks) {
+  return as_frag(*(const uint4*)(tile + row0 * kRowBytes + fa.rm[ks]));
+}
+// Transposed fragment: rows row0 + 8a + 4h + b (row0 a multiple of 16), columns 32 dt + l % 32.
+__device__ __forceinline__ bf16x8 frag_tr(const char* tile, const FragAddr& fa, int row0, int dt) {
+  typedef __attribute__((address_space(3))) s16x4* lds_p;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(tile + row0 * kRowBytes + fa.tr[dt][0]));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(tile + row0 * kRowBytes + fa.tr[dt][1]));
+  s16x8 v;
+  v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3]; v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Packs registers 8c .. 8c+7 of a C tile to bf16 (B operand of the next MFMA).
+__device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int c) {
+  bf16x8 p;
+#pragma unroll
+  for (int e = 0; e < 8; e++) p[e] = (__bf16)s[8 * c + e];
+  return p;
+}
+
+// Asynchronous global -> LDS copy of a 64-row tile (rows [row_start, row_start + 64) of a
+// [T, H, 128] bf16 tensor, head already applied to `base`), rows clamped to row_last so every
+// load reads real data.  global_load_lds_dwordx4 writes lane L's 16 bytes at (uniform LDS base)
+// + 16 L, so one wave instruction fills 4 consecutive tile rows; the swizzle is applied on the
+// global side: the lane that fills physical chunk p of a row fetches logical chunk p ^ swz(row).
+// Each of the 4 waves issues 4 of the 16 instructions of a tile.  Completion is tracked by
+// vmcnt; the data is visible to other waves after s_waitcnt vmcnt(0) + barrier.
+__device__ __forceinline__ void tile_load_async(char* tile, const bf16_t* base, int64_t stride_t, int row_start,
+                                                int row_last, int wave, int lane) {
+  typedef __attribute__((address_space(3))) void* lds_p;
+  typedef __attribute__((address_space(1))) const void* glb_p;
+#pragma unroll
+  for (int u = 0; u < 4; u++) {
+    const int n = wave * 4 + u;
+    const int row = 4 * n + (lane >> 4);
+    const int c16 = (lane & 15) ^ swz(row);
+    const int tok = min(row_start + row, row_last);
+    __builtin_amdgcn_global_load_lds((glb_p)(base + (int64_t)tok * stride_t + c16 * 8), (lds_p)(tile + n * 1024), 16, 0, 0);
+  }
+}
+
+// Two half-open key ranges of one query row, clipped to a KV block.
+struct RowRanges {
+  int lo1, n1, lo2, n2;  // start and length (0 when empty)
+  __device__ __forceinline__ bool sees(int key) const {
+    return (unsigned)(key - lo1) < (unsigned)n1 || (unsigned)(key - lo2) < (unsigned)n2;
+  }
+};
+
+// Effective ranges of query `i` (packed index) for one table row of kind `kind` over the block
+// [c0, c1); `r` holds the query's range array entry (RANGES only).
+__device__ __forceinline__ RowRanges row_ranges(int kind, int i, int c0, int c1, int4 r) {
+  RowRanges g;
+  int lo1 = c0, hi1 = c1, lo2 = 0, hi2 = 0;
+  if (kind == 1) hi1 = min(i + 1, c1);
+  if (kind == 2) { lo1 = max(r.x, c0); hi1 = min(r.y, c1); lo2 = max(r.z, c0); hi2 = min(r.w, c1); }
+  g.lo1 = lo1; g.n1 = max(hi1 - lo1, 0); g.lo2 = lo2; g.n2 = max(hi2 - lo2, 0);
+  return g;
+}
+
+// Bounds of a set of rows' range arrays: for each of the two ranges the smallest start, largest
+// start, smallest end, largest end over rows whose range is not empty (`any` = some row has one).
+struct RangeBounds {
+  int lo_min[2], lo_max[2], hi_min[2], hi_max[2];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int k = 0; k < 2; k++) { lo_min[k] = INT32_MAX; lo_max[k] = INT32_MIN; hi_min[k] = INT32_MAX; hi_max[k] = INT32_MIN; }
+  }
+  // rows with an empty range make "all rows cover the tile" impossible: lo_max = +inf
+  __device__ __forceinline__ void add(int4 r) {
+    const int lo[2] = {r.x, r.z}, hi[2] = {r.y, r.w};
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+      if (hi[k] > lo[k]) {
+        lo_min[k] = min(lo_min[k], lo[k]); lo_max[k] = max(lo_max[k], lo[k]);
+        hi_min[k] = min(hi_min[k], hi[k]); hi_max[k] = max(hi_max[k], hi[k]);
+      } else {
+        lo_max[k] = INT32_MAX; hi_min[k] = INT32_MIN;
+      }
+    }
+  }
+  __device__ __forceinline__ void wave_reduce() {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+#pragma unroll
+      for (int k = 0; k < 2; k++) {
+        lo_min[k] = min(lo_min[k], __shfl_xor(lo_min[k], off)); lo_max[k] = max(lo_max[k], __shfl_xor(lo_max[k], off));
+        hi_min[k] = min(hi_min[k], __shfl_xor(hi_min[k], off)); hi_max[k] = max(hi_max[k], __shfl_xor(hi_max[k], off));
+      }
+    }
+  }
+  // some row may see a key of [ks, ke)
+  __device__ __forceinline__ bool may_see(int ks, int ke) const {
+    return (ks < hi_max[0] && ke > lo_min[0]) || (ks < hi_max[1] && ke > lo_min[1]);
+  }
+  // every row sees every key of [ks, ke)
+  __device__ __forceinline__ bool all_see(int ks, int ke) const {
+    return (ks >= lo_max[0] && ke <= hi_min[0]) || (ks >= lo_max[1] && ke <= hi_min[1]);
+  }
+};
+
+enum TileClass { kSkip = 0, kFull = 1, kPartial = 2 };
+
+// Class of the key tile [ks, ks + 64) of the block ending at c1 for query rows [q_lo, q_hi]
+// (packed, inclusive, all valid) with range bounds rb.
+__device__ __forceinline__ int classify(int kind, int ks, int c1, int q_lo, int q_hi, const RangeBounds& rb) {
+  const int ke = min(ks + kTN, c1);
+  const bool whole = ks + kTN <= c1;
+  if (kind == 0) return whole ? kFull : kPartial;
+  if (kind == 1) {
+    if (ks > q_hi) return kSkip;
+    return (whole && ke - 1 <= q_lo) ? kFull : kPartial;
+  }
+  if (!rb.may_see(ks, ke)) return kSkip;
+  return (whole && rb.all_see(ks, ke)) ? kFull : kPartial;
+}
+
+// XCD-aware decode of the flat workgroup id: the grid is cut into 8 contiguous chunks of the
+// work order (kv head major, then item, then query head inside the group); chunk x runs on XCD x
+// because consecutive workgroup ids are dealt round-robin to the 8 XCDs.
+__device__ __forceinline__ bool decode_wg(int n_items, int heads_outer, int heads_inner, int* item, int* head) {
+  const int total = n_items * heads_outer * heads_inner;
+  const int per_xcd = (total + 7) >> 3;
+  const int w = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per_xcd || w >= total) return false;
+  const int hi = w % heads_inner;
+  *item = (w / heads_inner) % n_items;
+  *head = (w / (heads_inner * n_items)) * heads_inner + hi;
+  return true;
+}
+
+}  // namespace dcp
