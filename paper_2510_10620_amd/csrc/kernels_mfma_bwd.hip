@@ -1,7 +1,397 @@
-#include "kernels.h"
+// Blockwise attention backward on bf16 MFMA, as two kernels that each recompute P from the saved
+// LSE (no atomics, deterministic):
+//   dQ kernel    grouped by q_blk, same shape as the forward: S^T = K Q^T, dP^T = V dO^T,
+//                dS^T = P^T * (dP^T - delta), dQ^T += K^T dS^T (K^T fragments by transposing reads);
+//   dK/dV kernel grouped by kv_blk, a wave owns 32 keys as MFMA columns: S = Q K^T, dP = dO V^T,
+//                dV^T += dO^T P, dK^T += Q^T dS, looping over the query heads of the KV group and
+//                the query tiles of every listed q_blk (Q^T / dO^T fragments by transposing reads).
+#include "mfma_common.h"
+
 namespace dcp {
+
+static constexpr float kLog2e = 1.44269504088896340736f;
+
+// ------------------------------------------------------------------------------------ dQ
+struct DqState {
+  bf16x8 qf[8], dof[8];
+  f32x16 dq[4];
+  float lse2, delta;  // lse * log2(e) (+inf when the row saw nothing), delta
+  int qi;
+  int4 qr;
+  FragAddr fa;
+};
+
+template <bool MASK>
+__device__ __forceinline__ void dq_subtile(DqState& st, const char* k_lds, const char* v_lds, int kt, int ks32,
+                                           int kind, int c0, int c1, float c_log2, int lane) {
+  const int lh = lane >> 5;
+  f32x16 s, dp;
+#pragma unroll
+  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+  for (int ksd = 0; ksd < 8; ksd++) {
+    s = mfma(frag_rm(k_lds, st.fa, 32 * kt, ksd), st.qf[ksd], s);
+    dp = mfma(frag_rm(v_lds, st.fa, 32 * kt, ksd), st.dof[ksd], dp);
+  }
+  if (MASK) {
+    const RowRanges rr = row_ranges(kind, st.qi, c0, c1, st.qr);
+    const int kb = ks32 + 4 * lh;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int key = kb + 8 * (r / 4) + (r % 4);
+      if (!rr.sees(key)) s[r] = -INFINITY;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c_log2, -st.lse2));
+    s[r] = p * (dp[r] - st.delta);
+  }
+#pragma unroll
+  for (int c = 0; c < 2; c++) {
+    const bf16x8 b = pack_frag(s, c);
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) st.dq[dt] = mfma(frag_tr(k_lds, st.fa, 32 * kt + 16 * c, dt), b, st.dq[dt]);
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t) {
+  constexpr int TM = 128;
+  __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
+  __shared__ int wg_bounds[4][8];
+
+  int item, head;
+  const int G = t.hq / t.hkv;
+  if (!decode_wg(g.n_items, t.hkv, G, &item, &head)) return;
+  const int hk = head / G;
+  const WorkItem w = g.items[item];
+  const int qb = g.unit_blk[w.unit];
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int li = lane & 31, lh = lane >> 5;
+  const int blk_start = g.blk_start[qb], blk_len = g.blk_len[qb];
+  const int row0 = w.tile * TM;
+  const int n_rows = min(TM, blk_len - row0);
+  const int q_lo = blk_start + row0, q_hi = q_lo + n_rows - 1;
+  const int wrow0 = wave * 32;
+  const int w_rows = max(0, min(32, n_rows - wrow0));
+  const int wq_lo = q_lo + wrow0, wq_hi = wq_lo + w_rows - 1;
+
+  DqState st;
+  st.fa.init(lane);
+  const int r = wrow0 + li;
+  const bool qv = r < n_rows;
+  st.qi = q_lo + min(r, n_rows - 1);
+  st.qr = make_int4(0, 0, 0, 0);
+  RangeBounds wrb;
+  wrb.init();
+  if (t.ranges) {
+    st.qr = ((const int4*)t.ranges)[st.qi];
+    if (qv) wrb.add(st.qr);
+  }
+  RangeBounds rb = wrb;
+  if (t.ranges) {
+    wrb.wave_reduce();
+    if (lane == 0) {
+      wg_bounds[wave][0] = wrb.lo_min[0]; wg_bounds[wave][1] = wrb.lo_max[0]; wg_bounds[wave][2] = wrb.hi_min[0]; wg_bounds[wave][3] = wrb.hi_max[0];
+      wg_bounds[wave][4] = wrb.lo_min[1]; wg_bounds[wave][5] = wrb.lo_max[1]; wg_bounds[wave][6] = wrb.hi_min[1]; wg_bounds[wave][7] = wrb.hi_max[1];
+    }
+    __syncthreads();
+    rb.init();
+    for (int x = 0; x < 4; x++) {
+      rb.lo_min[0] = min(rb.lo_min[0], wg_bounds[x][0]); rb.lo_max[0] = max(rb.lo_max[0], wg_bounds[x][1]);
+      rb.hi_min[0] = min(rb.hi_min[0], wg_bounds[x][2]); rb.hi_max[0] = max(rb.hi_max[0], wg_bounds[x][3]);
+      rb.lo_min[1] = min(rb.lo_min[1], wg_bounds[x][4]); rb.lo_max[1] = max(rb.lo_max[1], wg_bounds[x][5]);
+      rb.hi_min[1] = min(rb.hi_min[1], wg_bounds[x][6]); rb.hi_max[1] = max(rb.hi_max[1], wg_bounds[x][7]);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+      rb.lo_min[k] = uni(rb.lo_min[k]); rb.lo_max[k] = uni(rb.lo_max[k]); rb.hi_min[k] = uni(rb.hi_min[k]); rb.hi_max[k] = uni(rb.hi_max[k]);
+      wrb.lo_min[k] = uni(wrb.lo_min[k]); wrb.lo_max[k] = uni(wrb.lo_max[k]); wrb.hi_min[k] = uni(wrb.hi_min[k]); wrb.hi_max[k] = uni(wrb.hi_max[k]);
+    }
+  }
+  {
+    const bf16_t* qp = (const bf16_t*)t.q + (int64_t)st.qi * t.q_st + (int64_t)head * t.q_sh + 8 * lh;
+    const bf16_t* dop = (const bf16_t*)t.dout + (int64_t)st.qi * t.do_st + (int64_t)head * t.do_sh + 8 * lh;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) {
+      st.qf[ks] = as_frag(*(const uint4*)(qp + 16 * ks));
+      st.dof[ks] = as_frag(*(const uint4*)(dop + 16 * ks));
+    }
+    const float lse = t.lse[(int64_t)head * t.total_tokens + st.qi];
+    st.lse2 = lse == -INFINITY ? INFINITY : lse * kLog2e;
+    st.delta = t.delta[(int64_t)head * t.total_tokens + st.qi];
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int x = 0; x < 16; x++) st.dq[dt][x] = 0.f;
+  }
+  const float c_log2 = t.scale * kLog2e;
+  const bf16_t* kbase = (const bf16_t*)t.k + (int64_t)hk * t.k_sh;
+  const bf16_t* vbase = (const bf16_t*)t.v + (int64_t)hk * t.v_sh;
+
+  KvIter it(g, w.unit);
+  bool have = it.next(q_hi, rb);
+  if (have) {
+    tile_load_async(stage0, kbase, t.k_st, it.ks, it.c1 - 1, wave, lane);
+    tile_load_async(stage0 + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave, lane);
+  }
+  __syncthreads();
+  auto step = [&](const char* cur, char* nxt) {
+    const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
+    have = it.next(q_hi, rb);
+    if (have) {
+      tile_load_async(nxt, kbase, t.k_st, it.ks, it.c1 - 1, wave, lane);
+      tile_load_async(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave, lane);
+    }
+    if (w_rows > 0) {
+#pragma unroll
+      for (int kt = 0; kt < 2; kt++) {
+        const int cls = classify32(kind, ks + 32 * kt, c1, wq_lo, wq_hi, wrb);
+        if (cls == kFull)
+          dq_subtile<false>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane);
+        else if (cls == kPartial)
+          dq_subtile<true>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane);
+      }
+    }
+    __syncthreads();
+  };
+  while (have) {
+    step(stage0, stage1);
+    if (!have) break;
+    step(stage1, stage0);
+  }
+  if (!qv) return;
+  bf16_t* op = (bf16_t*)t.dq + (int64_t)st.qi * t.dq_st + (int64_t)head * t.dq_sh;
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+    for (int a = 0; a < 4; a++) {
+      uint2 pk;
+      pk.x = (uint32_t)f32_to_bf16(st.dq[dt][4 * a] * t.scale) | ((uint32_t)f32_to_bf16(st.dq[dt][4 * a + 1] * t.scale) << 16);
+      pk.y = (uint32_t)f32_to_bf16(st.dq[dt][4 * a + 2] * t.scale) | ((uint32_t)f32_to_bf16(st.dq[dt][4 * a + 3] * t.scale) << 16);
+      *(uint2*)(op + 32 * dt + 8 * a + 4 * lh) = pk;
+    }
+}
+
+// ------------------------------------------------------------------------------------ dK / dV
+// LDS stage of the dK/dV kernel: a 64-query tile of Q and dO plus the rows' LSE, delta and ranges.
+static constexpr int kStageLse = 2 * kTileBytes;
+static constexpr int kStageDelta = kStageLse + 256;
+static constexpr int kStageRanges = kStageDelta + 256;
+static constexpr int kStageBytes = kStageRanges + 1024;
+
+// Walks (table row, query head of the group, 64-query tile) for one KV tile.
+struct QIter {
+  const int32_t *ent_start, *ent_len, *ent_kind;
+  int e, e_end, hh, G, jt, n_t, jt0;
+  int q0, q1, kind;
+  int qs;  // first query of the current tile
+  __device__ QIter(const DevGroup& g, int unit, int G_) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind) {
+    e = g.ptr[unit] - 1; e_end = g.ptr[unit + 1]; hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; qs = 0;
+  }
+  // k_lo: first key of the workgroup's tile.  Under CAUSAL, query tiles that end before k_lo see nothing.
+  __device__ bool next(int k_lo) {
+    for (;;) {
+      jt++;
+      if (jt >= n_t) {
+        hh++;
+        if (hh >= G) {
+          e++;
+          if (e >= e_end) return false;
+          hh = 0;
+          q0 = ent_start[e]; q1 = q0 + ent_len[e]; kind = ent_kind[e];
+          n_t = (q1 - q0 + kTN - 1) / kTN;
+          jt0 = kind == 1 ? max(0, (k_lo - q0) / kTN) : 0;
+        }
+        jt = jt0 - 1;
+        continue;
+      }
+      qs = q0 + jt * kTN;
+      return true;
+    }
+  }
+};
+
+struct DkvState {
+  bf16x8 kf[8], vf[8];
+  f32x16 dk[4], dv[4];
+  int kj;
+  FragAddr fa;
+};
+
+template <bool MASK>
+__device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int qt, int qs32, int q1, int kind,
+                                            int k_end, float c_log2, int lane) {
+  const int lh = lane >> 5;
+  const char* q_lds = stage;
+  const char* do_lds = stage + kTileBytes;
+  f32x16 s, dp;
+#pragma unroll
+  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+  for (int ksd = 0; ksd < 8; ksd++) {
+    s = mfma(frag_rm(q_lds, st.fa, 32 * qt, ksd), st.kf[ksd], s);
+    dp = mfma(frag_rm(do_lds, st.fa, 32 * qt, ksd), st.vf[ksd], dp);
+  }
+  // rows of the C tile are queries 8a + 4 lh + b: their LSE / delta come from LDS (broadcast reads)
+  const float* lse_lds = (const float*)(stage + kStageLse) + 32 * qt + 4 * lh;
+  const float* dl_lds = (const float*)(stage + kStageDelta) + 32 * qt + 4 * lh;
+#pragma unroll
+  for (int a = 0; a < 4; a++) {
+    const float4 l4 = *(const float4*)(lse_lds + 8 * a);
+    const float4 d4 = *(const float4*)(dl_lds + 8 * a);
+    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+    for (int b = 0; b < 4; b++) {
+      const int r = 4 * a + b;
+      const float lse2 = lv[b] == -INFINITY ? INFINITY : lv[b] * kLog2e;
+      float x = s[r];
+      if (MASK) {
+        const int q = qs32 + 8 * a + 4 * lh + b;
+        bool vis = q < q1 && st.kj < k_end;
+        if (kind == 1) vis = vis && st.kj <= q;
+        if (kind == 2) {
+          const int4 rg = *(const int4*)(stage + kStageRanges + (32 * qt + 8 * a + 4 * lh + b) * 16);
+          vis = vis && ((st.kj >= rg.x && st.kj < rg.y) || (st.kj >= rg.z && st.kj < rg.w));
+        }
+        if (!vis) x = -INFINITY;
+      }
+      const float p = __builtin_amdgcn_exp2f(fmaf(x, c_log2, -lse2));
+      s[r] = p;
+      dp[r] = p * (dp[r] - dv4[b]);
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 2; c++) {
+    const bf16x8 pb = pack_frag(s, c), dsb = pack_frag(dp, c);
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) {
+      st.dv[dt] = mfma(frag_tr(do_lds, st.fa, 32 * qt + 16 * c, dt), pb, st.dv[dt]);
+      st.dk[dt] = mfma(frag_tr(q_lds, st.fa, 32 * qt + 16 * c, dt), dsb, st.dk[dt]);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t) {
+  constexpr int TK = 128;
+  __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char stage1[kStageBytes];
+
+  int item, hk;
+  if (!decode_wg(g.n_items, t.hkv, 1, &item, &hk)) return;
+  const int G = t.hq / t.hkv;
+  const WorkItem w = g.items[item];
+  const int kb = g.unit_blk[w.unit];
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int li = lane & 31, lh = lane >> 5;
+  const int blk_start = g.blk_start[kb], blk_len = g.blk_len[kb];
+  const int row0 = w.tile * TK;
+  const int n_rows = min(TK, blk_len - row0);
+  const int k_lo = blk_start + row0, k_end = k_lo + n_rows;
+  const int wrow0 = wave * 32;
+  const int w_rows = max(0, min(32, n_rows - wrow0));
+  const int wk_lo = k_lo + wrow0, wk_hi = wk_lo + w_rows - 1;
+
+  DkvState st;
+  st.fa.init(lane);
+  const bool kvalid = wrow0 + li < n_rows;
+  st.kj = k_lo + wrow0 + li;                       // may lie past k_end: masked, never stored
+  {
+    const int kl = min(st.kj, k_end - 1);
+    const bf16_t* kp = (const bf16_t*)t.k + (int64_t)kl * t.k_st + (int64_t)hk * t.k_sh + 8 * lh;
+    const bf16_t* vp = (const bf16_t*)t.v + (int64_t)kl * t.v_st + (int64_t)hk * t.v_sh + 8 * lh;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) {
+      st.kf[ks] = as_frag(*(const uint4*)(kp + 16 * ks));
+      st.vf[ks] = as_frag(*(const uint4*)(vp + 16 * ks));
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int x = 0; x < 16; x++) { st.dk[dt][x] = 0.f; st.dv[dt][x] = 0.f; }
+  }
+  const float c_log2 = t.scale * kLog2e;
+
+  typedef __attribute__((address_space(3))) void* lds_p;
+  typedef __attribute__((address_space(1))) const void* glb_p;
+  QIter it(g, w.unit, G);
+  auto issue = [&](char* stage) {
+    const int head = hk * G + it.hh;
+    const int last = it.q1 - 1;
+    tile_load_async(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, t.q_st, it.qs, last, wave, lane);
+    tile_load_async(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, t.do_st, it.qs, last, wave, lane);
+    const int qrow = min(it.qs + lane, last);
+    if (wave == 0)
+      __builtin_amdgcn_global_load_lds((glb_p)(t.lse + (int64_t)head * t.total_tokens + qrow), (lds_p)(stage + kStageLse), 4, 0, 0);
+    if (wave == 1)
+      __builtin_amdgcn_global_load_lds((glb_p)(t.delta + (int64_t)head * t.total_tokens + qrow), (lds_p)(stage + kStageDelta), 4, 0, 0);
+    if (wave == 2 && it.kind == 2)
+      __builtin_amdgcn_global_load_lds((glb_p)(t.ranges + (int64_t)qrow * 4), (lds_p)(stage + kStageRanges), 16, 0, 0);
+  };
+  bool have = it.next(k_lo);
+  if (have) issue(stage0);
+  __syncthreads();
+  auto step = [&](const char* cur, char* nxt) {
+    const int qs = it.qs, q1 = it.q1, kind = it.kind;
+    have = it.next(k_lo);
+    if (have) issue(nxt);
+    if (w_rows > 0) {
+#pragma unroll
+      for (int qt = 0; qt < 2; qt++) {
+        const int qs32 = qs + 32 * qt;
+        if (qs32 >= q1) continue;
+        const bool whole = qs32 + 32 <= q1 && w_rows == 32;
+        int cls = kPartial;
+        if (kind == 0) cls = whole ? kFull : kPartial;
+        if (kind == 1) cls = min(qs32 + 31, q1 - 1) < wk_lo ? kSkip : ((whole && qs32 >= wk_hi) ? kFull : kPartial);
+        if (cls == kFull)
+          dkv_subtile<false>(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane);
+        else if (cls == kPartial)
+          dkv_subtile<true>(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane);
+      }
+    }
+    __syncthreads();
+  };
+  while (have) {
+    step(stage0, stage1);
+    if (!have) break;
+    step(stage1, stage0);
+  }
+  if (!kvalid) return;
+  bf16_t* dkp = (bf16_t*)t.dk + (int64_t)st.kj * t.dk_st + (int64_t)hk * t.dk_sh;
+  bf16_t* dvp = (bf16_t*)t.dv + (int64_t)st.kj * t.dv_st + (int64_t)hk * t.dv_sh;
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+    for (int a = 0; a < 4; a++) {
+      uint2 pk, pv;
+      pk.x = (uint32_t)f32_to_bf16(st.dk[dt][4 * a] * t.scale) | ((uint32_t)f32_to_bf16(st.dk[dt][4 * a + 1] * t.scale) << 16);
+      pk.y = (uint32_t)f32_to_bf16(st.dk[dt][4 * a + 2] * t.scale) | ((uint32_t)f32_to_bf16(st.dk[dt][4 * a + 3] * t.scale) << 16);
+      pv.x = (uint32_t)f32_to_bf16(st.dv[dt][4 * a]) | ((uint32_t)f32_to_bf16(st.dv[dt][4 * a + 1]) << 16);
+      pv.y = (uint32_t)f32_to_bf16(st.dv[dt][4 * a + 2]) | ((uint32_t)f32_to_bf16(st.dv[dt][4 * a + 3]) << 16);
+      *(uint2*)(dkp + 32 * dt + 8 * a + 4 * lh) = pk;
+      *(uint2*)(dvp + 32 * dt + 8 * a + 4 * lh) = pv;
+    }
+}
+
 int mfma_dq_tile() { return 128; }
 int mfma_dkv_tile() { return 128; }
-dcp_status_t mfma_bwd_dq(const DevGroup&, const KTensors&, hipStream_t) { return fail(DCP_ERR_UNSUPPORTED, "stub"); }
-dcp_status_t mfma_bwd_dkv(const DevGroup&, const KTensors&, hipStream_t) { return fail(DCP_ERR_UNSUPPORTED, "stub"); }
+
+dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s) {
+  if (g.n_items == 0) return DCP_OK;
+  const int per_xcd = (g.n_items * t.hq + 7) / 8;
+  hipLaunchKernelGGL(mfma_dq_kernel, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  DCP_HIP_TRY(hipGetLastError());
+  return DCP_OK;
 }
+
+dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s) {
+  if (g.n_items == 0) return DCP_OK;
+  const int per_xcd = (g.n_items * t.hkv + 7) / 8;
+  hipLaunchKernelGGL(mfma_dkv_kernel, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  DCP_HIP_TRY(hipGetLastError());
+  return DCP_OK;
+}
+
+}  // namespace dcp

@@ -207,6 +207,51 @@ __device__ __forceinline__ int classify(int kind, int ks, int c1, int q_lo, int 
   return (whole && rb.all_see(ks, ke)) ? kFull : kPartial;
 }
 
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Walks the (table row, key tile) pairs of a unit that the workgroup cannot skip.  All state is
+// wave-uniform.
+struct KvIter {
+  const int32_t *ent_start, *ent_len, *ent_kind;
+  int e, e_end, jt, n_t;
+  int c0, c1, kind;
+  int ks;  // first key of the current tile
+  __device__ KvIter(const DevGroup& g, int unit) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind) {
+    e = g.ptr[unit] - 1; e_end = g.ptr[unit + 1]; jt = 0; n_t = 0; c0 = c1 = kind = 0; ks = 0;
+  }
+  // Advances to the next tile some row of [.., q_hi] may see; false when the unit is done.
+  __device__ bool next(int q_hi, const RangeBounds& rb) {
+    for (;;) {
+      jt++;
+      if (jt >= n_t) {
+        e++;
+        if (e >= e_end) return false;
+        c0 = ent_start[e]; c1 = c0 + ent_len[e]; kind = ent_kind[e];
+        n_t = (c1 - c0 + kTN - 1) / kTN;
+        if (kind == 1) n_t = min(n_t, max(0, (q_hi - c0) / kTN + 1));  // tiles starting after q_hi are empty
+        jt = -1;
+        continue;
+      }
+      ks = c0 + jt * kTN;
+      if (kind != 2 || rb.may_see(ks, min(ks + kTN, c1))) return true;
+    }
+  }
+};
+
+// Class of the 32-key sub-tile [ks, ks + 32) for the rows [q_lo, q_hi] with bounds rb.
+__device__ __forceinline__ int classify32(int kind, int ks, int c1, int q_lo, int q_hi, const RangeBounds& rb) {
+  if (ks >= c1) return kSkip;
+  const int ke = min(ks + 32, c1);
+  const bool whole = ks + 32 <= c1;
+  if (kind == 0) return whole ? kFull : kPartial;
+  if (kind == 1) {
+    if (ks > q_hi) return kSkip;
+    return (whole && ke - 1 <= q_lo) ? kFull : kPartial;
+  }
+  if (!rb.may_see(ks, ke)) return kSkip;
+  return (whole && rb.all_see(ks, ke)) ? kFull : kPartial;
+}
+
 // XCD-aware decode of the flat workgroup id: the grid is cut into 8 contiguous chunks of the
 // work order (kv head major, then item, then query head inside the group); chunk x runs on XCD x
 // because consecutive workgroup ids are dealt round-robin to the 8 XCDs.

@@ -94,24 +94,51 @@ def oracle_full(w, tensors, table, select=None, lse=None, delta=None, bwd=True, 
     return res
 
 
+def _cmp_mask(a, b):
+    same_inf = np.isinf(b) & (a == b)
+    return ~np.isnan(b) & ~same_inf
+
+
 def max_abs(a, b):
     """Max abs difference where the reference b is finite or both are equal infinities; positions
     where b is NaN (not computed by the oracle) are ignored."""
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
-    same_inf = np.isinf(b) & (a == b)
-    cmp = ~np.isnan(b) & ~same_inf
+    cmp = _cmp_mask(a, b)
     if not cmp.any():
         return 0.0
     d = np.abs(a[cmp] - b[cmp])
     return float(np.nan_to_num(d, nan=np.inf, posinf=np.inf).max())
 
 
-TOL = {"bf16": dict(o=2e-2, lse=1e-5), "f32": dict(o=1e-4, lse=1e-5)}
+def max_scaled(a, b, knee):
+    """max |a - b| / max(1, |b| / knee): the absolute error where |b| <= knee, and the error
+    relative to |b| / knee above it."""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    cmp = _cmp_mask(a, b)
+    if not cmp.any():
+        return 0.0
+    d = np.abs(a[cmp] - b[cmp]) / np.maximum(1.0, np.abs(b[cmp]) / knee)
+    return float(np.nan_to_num(d, nan=np.inf, posinf=np.inf).max())
 
 
-def check(w, got, ref, names, label=""):
+# Tolerances.  LSE (fp32): max abs 1e-5.  fp32 I/O: max abs 1e-4.  bf16 I/O: max abs 2e-2 for
+# |reference| <= 2.  Above that the bf16 output grid itself approaches and then exceeds 2e-2
+# (half an ulp is 2^-8 |x|: 0.0156 on [4, 8), 0.031 on [8, 16)), and the bf16 rounding of the
+# P / dS MFMA operands adds its own accumulated share, so the bound grows in proportion to the
+# magnitude: 2e-2 * |ref| / 2 = 1e-2 |ref|, about 2.5 bf16 half-ulps.
+TOL = {"bf16": dict(o=2e-2, lse=1e-5, knee=2.0), "f32": dict(o=1e-4, lse=1e-5, knee=None)}
+
+
+def check(w, got, ref, names, label="", verbose=False):
     tol = TOL[w.dtype]
+    errs = {}
     for n in names:
-        err = max_abs(got[n], ref[n])
-        lim = tol["lse"] if n == "lse" else tol["o"]
-        assert err <= lim, f"{label} {n}: max abs err {err:.3e} > {lim:.1e}"
+        if n == "lse" or tol["knee"] is None:
+            err, lim = max_abs(got[n], ref[n]), (tol["lse"] if n == "lse" else tol["o"])
+        else:
+            err, lim = max_scaled(got[n], ref[n], tol["knee"]), tol["o"]
+        errs[n] = err
+        assert err <= lim, f"{label} {n}: max err {err:.3e} > {lim:.1e}"
+    if verbose:
+        print(label, {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    return errs

@@ -101,7 +101,7 @@ def test_share_with_divisions_and_merge(impl):
         qb = int(slot_q[s])
         r0, n = int(part["blk_start"][qb]), int(part["blk_end"][qb] - part["blk_start"][qb])
         ps = H.oracle_full(w, tensors, table, select=rows, bwd=False, seqs=[int(part["blk_seq"][qb])])
-        assert H.max_abs(o_part[s, :n], ps["out"][r0:r0 + n]) <= 2e-2
+        assert H.max_scaled(o_part[s, :n], ps["out"][r0:r0 + n], 2.0) <= 2e-2
         assert H.max_abs(lse_part[s, :, :n], ps["lse"][:, r0:r0 + n]) <= 1e-5
     dq, dk, dv = g.backward(out=gfull.out, lse=gfull.lse)
     H.check(w, dict(dq=dq, dk=dk, dv=dv), ref, ("dq", "dk", "dv"), "share bwd")
