@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the hot path over one synthetic packed batch of the causal varlen bf16
+configuration (32/8 heads, D 128, 65 536 tokens, log-normal lengths, block 1024): forward, then
+backward (delta, dQ, dK/dV kernels).  Inputs are resident in HBM and the plan is created before
+the timed region.  Prints ONE JSON line: effective TFLOP/s counting 14*D flops per visible
+(query, key) pair per query head, the roofline of the dominant kernel from HIP events recorded
+around every kernel launch, and the CPU oracle timed on a bounded sample of the same batch.
+A second, shorter section times one device's share of a plan (partial slots + LSE merge) so that
+the merge and the streaming kernels are measured too; it is reported under "extra".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 2.4 GHz x 4096 flop/clk/CU, dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0
+
+
+def gen_tensors(torch, w, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    T = w.total_tokens
+    mk = lambda h, sc: (torch.randn((T, h, w.d), device="cuda", generator=g, dtype=torch.float32) * sc).to(torch.bfloat16)
+    return mk(w.hq, w.input_scale), mk(w.hkv, w.input_scale), mk(w.hkv, w.input_scale), mk(w.hq, 1.0)
+
+
+def time_steps(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline(w, table, q, k, v, do, budget_pairs=6.0e7):
+    """The oracle as it stands, timed on the first sequences of the batch (until their dense
+    L^2 reaches the budget) for the 4 query heads of KV group 0, forward + backward."""
+    import numpy as np
+    from oracle import attention as OA
+    from oracle import blocks as OB
+    cu = w.cu_seqlens
+    seqs, dense = [], 0.0
+    for s in range(len(cu) - 1):
+        L = int(cu[s + 1] - cu[s])
+        if seqs and dense + float(L) * L > budget_pairs:
+            continue
+        seqs.append(s)
+        dense += float(L) * L
+        if dense >= 0.8 * budget_pairs:
+            break
+    G = w.hq // w.hkv
+    hi = int(cu[max(seqs) + 1])
+    qh = q[:hi, :G].double().cpu().numpy()
+    kh = k[:hi, :1].double().cpu().numpy()
+    vh = v[:hi, :1].double().cpu().numpy()
+    doh = do[:hi, :G].double().cpu().numpy()
+    vis = OB.Visibility(cu, w.block_size, table, w.ranges)
+    pairs = 0
+    for s in seqs:
+        L = int(cu[s + 1] - cu[s])
+        pairs += L * (L + 1) // 2 if w.mask.kind == "causal" else int(vis.rows(s, 0, L).sum())
+    t0 = time.perf_counter()
+    OA.attention_fwd(qh, kh, vh, cu, vis, w.softmax_scale, seqs=seqs)
+    OA.attention_bwd(qh, kh, vh, doh, cu, vis, w.softmax_scale, seqs=seqs)
+    dt = time.perf_counter() - t0
+    flops = pairs * G * w.d * 14
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    return dict(value=flops / dt / 1e12, unit="TFLOP/s", cores=int(threads), kind="oracle", seconds=round(dt, 2),
+                sample=f"sequences {seqs} of the batch ({sum(int(cu[s+1]-cu[s]) for s in seqs)} tokens), "
+                       f"the {G} query heads of KV head 0, fp64 dense forward + backward; "
+                       f"{pairs} visible pairs x {G} heads x 14*D flops")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2510_10620_amd as P
+    from paper_2510_10620_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    w = W.make_workload(args.config)
+    table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+    pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, table, w.ranges).sum())
+    q, k, v, do = gen_tensors(torch, w, w.tensor_seed)
+    T = w.total_tokens
+    out = torch.empty_like(q)
+    lse = torch.empty((w.hq, T), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+    t0 = time.perf_counter()
+    plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plan, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
+
+    def step():
+        P.dcp_block_attn_fwd(plan, q, k, v, out, lse, w.softmax_scale, rg)
+        P.dcp_block_attn_bwd(plan, q, k, v, out, lse, do, dq, dk, dv, w.softmax_scale, ws, rg)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    P.dcp_profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    P.dcp_profile_enable(False)
+
+    unit = pairs * w.hq * w.d            # one "D flops per pair per head" unit
+    flops = 14 * unit
+    # algorithmic flops per launch: forward 4D; the backward's 10D split over its two kernels as
+    # dK/dV: dV + dK + half of the shared (S, dP) recompute = 6D;  dQ: dQ + the other half = 4D
+    alg = dict(fwd=4 * unit, dq=4 * unit, dkv=6 * unit)
+    executed = dict(fwd=4 * unit, dq=6 * unit, dkv=8 * unit)
+    kern = {}
+    for name in ("fwd", "delta", "dq", "dkv"):
+        tot, n = P.dcp_profile_read(name)
+        kern[name] = dict(ms=tot / max(n, 1), launches=n)
+    dom = max(("fwd", "dq", "dkv"), key=lambda n: kern[n]["ms"])
+    ach = alg[dom] / (kern[dom]["ms"] * 1e-3) / 1e12
+    roofline = dict(kernel={"fwd": "mfma_fwd_kernel", "dq": "mfma_dq_kernel", "dkv": "mfma_dkv_kernel"}[dom],
+                    bound="mfma", achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    executed_tflops=round(executed[dom] / (kern[dom]["ms"] * 1e-3) / 1e12, 1))
+    delta_bytes = T * w.hq * (4 * w.d + 4)
+    per_kernel = {n: dict(ms=round(kern[n]["ms"], 4),
+                          tflops=round(alg[n] / (kern[n]["ms"] * 1e-3) / 1e12, 1) if n in alg else None)
+                  for n in kern}
+    per_kernel["delta"]["GBps"] = round(delta_bytes / (kern["delta"]["ms"] * 1e-3) / 1e9, 1)
+    per_kernel["delta"]["frac_hbm"] = round(per_kernel["delta"]["GBps"] / PEAK_HBM_GBPS, 3)
+
+    extra = dict(per_kernel=per_kernel, plan_create_ms=round(plan_ms, 3), visible_pairs=pairs,
+                 table_rows=int(len(table)), n_seq=int(len(w.cu_seqlens) - 1))
+    if not args.no_extra:
+        extra["share"] = share_section(torch, P, W, np, steps=max(3, args.steps // 4), warmup=2)
+
+    value = flops / (ms * 1e-3) / 1e12
+    line = dict(metric="effective attention TFLOP/s fwd+bwd (unmasked FLOPs) and % of bf16 MFMA peak",
+                value=round(value, 1), unit="TFLOP/s", pct_of_bf16_mfma_peak=round(100 * value / PEAK_BF16_TFLOPS, 2),
+                n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=round(ms, 4), higher_is_better=True,
+                scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+                config=dict(workload=f"config {args.config}: {w.name}, {T} packed tokens in {len(w.cu_seqlens) - 1} "
+                                     f"sequences, {w.hq}/{w.hkv} heads, D {w.d}, block {w.block_size}, mask {w.mask.kind}",
+                            global_batch_tokens=T, block_size=w.block_size, parallelism="single GPU"),
+                roofline=roofline, extra=extra)
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, table, q, k, v, do)
+    print(json.dumps(line))
+
+
+def share_section(torch, P, W, np, steps, warmup):
+    """One device's share (1/8 of the computation blocks, 4 divisions) of the 262 144-token causal
+    plan: forward into partial slots, LSE merge, backward of the share.  Times the merge kernel
+    against HBM bandwidth."""
+    w = W.make_workload(5)
+    table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+    n_shares, share_seed, n_div, div_seed = w.share
+    sel = W.deal_share(len(table), n_shares, share_seed, 0)
+    sub = table[sel]
+    slot, n_slots, slot_q = W.deal_divisions(sub[:, 0], n_div, div_seed)
+    pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, sub, w.ranges).sum())
+    q, k, v, do = gen_tensors(torch, w, w.tensor_seed)
+    T = w.total_tokens
+    plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, sub, slot, n_slots)
+    o_part = torch.empty((n_slots, w.block_size, w.hq, w.d), dtype=torch.bfloat16, device="cuda")
+    lse_part = torch.empty((n_slots, w.hq, w.block_size), dtype=torch.float32, device="cuda")
+    out = torch.empty_like(q)
+    lse = torch.empty((w.hq, T), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+    ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plan, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
+    # global O / LSE for the share's backward: an untimed full-table forward
+    full = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)
+    out_g, lse_g = torch.empty_like(q), torch.empty_like(lse)
+    P.dcp_block_attn_fwd(full, q, k, v, out_g, lse_g, w.softmax_scale, rg)
+    torch.cuda.synchronize()
+
+    def step():
+        P.dcp_block_attn_fwd(plan, q, k, v, o_part, lse_part, w.softmax_scale, rg)
+        P.dcp_merge_partials(plan, o_part, lse_part, out, lse)
+        P.dcp_block_attn_bwd(plan, q, k, v, out_g, lse_g, do, dq, dk, dv, w.softmax_scale, ws, rg)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    P.dcp_profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    P.dcp_profile_enable(False)
+    res = dict(workload=f"config 5: share 0 of {n_shares} of a {T}-token causal plan, {len(sub)} of {len(table)} "
+                        f"computation blocks, {n_div} divisions -> {n_slots} partial slots, block {w.block_size}",
+               ms_per_step=round(ms, 4), tflops=round(14 * pairs * w.hq * w.d / (ms * 1e-3) / 1e12, 1), steps=steps)
+    blk_len = plan.export("BLK_LEN").astype(np.int64)
+    mptr = plan.export("MERGE_PTR").astype(np.int64)
+    rowhead = w.hq * (2 * w.d + 4)
+    merge_bytes = int((blk_len * (np.diff(mptr) + 1)).sum()) * rowhead
+    for name in ("fwd", "merge", "delta", "dq", "dkv"):
+        tot, n = P.dcp_profile_read(name)
+        res[name + "_ms"] = round(tot / max(n, 1), 4)
+    res["merge_GBps"] = round(merge_bytes / (res["merge_ms"] * 1e-3) / 1e9, 1)
+    res["merge_frac_hbm"] = round(res["merge_GBps"] / PEAK_HBM_GBPS, 3)
+    return res
+
+
+if __name__ == "__main__":
+    main()

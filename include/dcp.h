@@ -184,6 +184,15 @@ dcp_status_t dcp_sum_partials(const void* const* parts_host_array_of_device_ptrs
                               int32_t parts_dtype, void* dst, int32_t dst_dtype, int64_t n_elems,
                               void* stream);
 
+/* Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
+ * bracketed by hipEvents recorded on the launch stream (the kernels of one backward call are timed
+ * one by one).  dcp_profile_read synchronises on the recorded events, returns the summed duration
+ * and the number of launches of one kernel since the last enable, and leaves the records in place;
+ * dcp_profile_enable(1) clears them.  Not thread-safe; meant for a single benchmarking thread. */
+typedef enum { DCP_K_FWD = 0, DCP_K_MERGE = 1, DCP_K_DELTA = 2, DCP_K_DQ = 3, DCP_K_DKV = 4, DCP_K_SUM = 5 } dcp_kernel_id_t;
+dcp_status_t dcp_profile_enable(int32_t enable);
+dcp_status_t dcp_profile_read(int32_t kernel_id, double* total_ms, int64_t* launches);
+
 /* Last error message of the calling thread ("" if none). */
 const char* dcp_last_error(void);
 

@@ -34,8 +34,18 @@ def _softmax_rows(S):
     return lse, P
 
 
-def attention_fwd(q, k, v, cu_seqlens, vis, scale, seqs=None, row_chunk=2048):
-    """Returns (O [T,Hq,D], LSE [Hq,T]).  Sequences not in `seqs` are left NaN."""
+def _row_span(rows, s, L):
+    """Query-row window [r0, r1) of sequence s: the whole sequence unless `rows` (a dict
+    sequence -> (r0, r1)) narrows it."""
+    if rows is None or s not in rows:
+        return 0, L
+    r0, r1 = rows[s]
+    return max(0, int(r0)), min(L, int(r1))
+
+
+def attention_fwd(q, k, v, cu_seqlens, vis, scale, seqs=None, row_chunk=2048, rows=None):
+    """Returns (O [T,Hq,D], LSE [Hq,T]).  Sequences not in `seqs`, and query rows outside the
+    window `rows[s]`, are left NaN."""
     q, k, v = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
     T, Hq, D = q.shape
     G = Hq // k.shape[1]
@@ -44,8 +54,9 @@ def attention_fwd(q, k, v, cu_seqlens, vis, scale, seqs=None, row_chunk=2048):
     LSE = np.full((Hq, T), np.nan)
     for s in (range(len(cu) - 1) if seqs is None else seqs):
         b, e = int(cu[s]), int(cu[s + 1])
-        for r0 in range(0, e - b, row_chunk):
-            r1 = min(e - b, r0 + row_chunk)
+        w0, w1 = _row_span(rows, s, e - b)
+        for r0 in range(w0, w1, row_chunk):
+            r1 = min(w1, r0 + row_chunk)
             M = vis.rows(s, r0, r1)
             for h in range(Hq):
                 S = _scores(q[b + r0:b + r1, h], k[b:e, h // G], scale, M)
@@ -61,14 +72,16 @@ def delta_rows(o, do):
 
 
 def attention_bwd(q, k, v, do, cu_seqlens, vis, scale, lse=None, delta=None, seqs=None,
-                  row_chunk=2048):
+                  row_chunk=2048, rows=None):
     """Gradients (dQ, dK, dV) of sum(O * dO).
 
     With lse/delta None they are derived from `vis` itself (plain full attention).  For one
     device's share of the computation blocks, pass the *global* LSE and Delta (of the merged
     output) and a `vis` restricted to the share: P = exp(S - LSE) on the share's visible pairs,
     dV = P^T dO, dP = dO V^T, dS = P * (dP - Delta), dQ = scale dS K, dK = scale dS^T Q; the
-    KV-head gradients sum over the query heads of the group.  Sequences not in `seqs` stay NaN."""
+    KV-head gradients sum over the query heads of the group.  Sequences not in `seqs` stay NaN.
+    With a query-row window `rows[s]`, dQ is filled for those rows only and dK / dV hold the
+    contributions of those query rows only (complete for a key all of whose viewers lie inside)."""
     q, k, v, do = (np.asarray(a, dtype=np.float64) for a in (q, k, v, do))
     T, Hq, D = q.shape
     Hkv = k.shape[1]
@@ -81,8 +94,9 @@ def attention_bwd(q, k, v, do, cu_seqlens, vis, scale, lse=None, delta=None, seq
         b, e = int(cu[s]), int(cu[s + 1])
         dk[b:e] = 0.0
         dv[b:e] = 0.0
-        for r0 in range(0, e - b, row_chunk):
-            r1 = min(e - b, r0 + row_chunk)
+        w0, w1 = _row_span(rows, s, e - b)
+        for r0 in range(w0, w1, row_chunk):
+            r1 = min(w1, r0 + row_chunk)
             M = vis.rows(s, r0, r1)
             sl = slice(b + r0, b + r1)
             for h in range(Hq):

@@ -193,3 +193,18 @@ def dcp_sum_partials(parts, dst):
     arr = (ctypes.c_void_p * len(parts))(*[p.data_ptr() for p in parts])
     _check(_lib.load().dcp_sum_partials(arr, len(parts), _dtype_code(parts[0]), dst.data_ptr(), _dtype_code(dst),
                                         dst.numel(), _stream()))
+
+
+KERNEL_IDS = dict(fwd=0, merge=1, delta=2, dq=3, dkv=4, sum=5)
+
+
+def dcp_profile_enable(enable):
+    _check(_lib.load().dcp_profile_enable(1 if enable else 0))
+
+
+def dcp_profile_read(kernel):
+    """-> (total_ms, launches) of one kernel since dcp_profile_enable(True)."""
+    kid = KERNEL_IDS[kernel] if isinstance(kernel, str) else int(kernel)
+    ms, n = ctypes.c_double(0), ctypes.c_int64(0)
+    _check(_lib.load().dcp_profile_read(kid, ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value

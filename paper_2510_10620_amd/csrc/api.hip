@@ -1,10 +1,52 @@
 // Launching entry points of the C ABI: argument validation (host side, complete before any
 // launch), kernel-family selection, and the enqueue of the kernels on the caller's stream.
 #include <cmath>
+#include <vector>
 
 #include "kernels.h"
 
 using namespace dcp;
+
+namespace dcp {
+struct ProfRec { hipEvent_t a, b; };
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof[6];
+ProfScope::ProfScope(int id_, hipStream_t s_) : id(id_), s(s_) {
+  if (!g_prof_on) return;
+  hipEvent_t a = nullptr;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { stop = nullptr; return; }
+  (void)hipEventRecord(a, s);
+  g_prof[id].push_back({a, stop});
+}
+ProfScope::~ProfScope() {
+  if (stop) (void)hipEventRecord(stop, s);
+}
+}  // namespace dcp
+
+extern "C" dcp_status_t dcp_profile_enable(int32_t enable) {
+  if (enable) {
+    for (auto& v : g_prof) {
+      for (auto& r : v) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+      v.clear();
+    }
+  }
+  g_prof_on = enable != 0;
+  return DCP_OK;
+}
+
+extern "C" dcp_status_t dcp_profile_read(int32_t kernel_id, double* total_ms, int64_t* launches) {
+  if (kernel_id < 0 || kernel_id > 5 || !total_ms || !launches) return fail(DCP_ERR_INVALID_ARG, "bad kernel id or NULL output");
+  double tot = 0;
+  for (auto& r : g_prof[kernel_id]) {
+    DCP_HIP_TRY(hipEventSynchronize(r.b));
+    float ms = 0;
+    DCP_HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = (int64_t)g_prof[kernel_id].size();
+  return DCP_OK;
+}
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -75,6 +117,7 @@ extern "C" dcp_status_t dcp_block_attn_fwd(dcp_plan_t* plan, const dcp_tensors_t
   DevGroup g;
   if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g)) != DCP_OK) return st;
   KTensors k = pack(plan, t);
+  ProfScope ps(DCP_K_FWD, s);
   return use_mfma ? mfma_fwd(g, k, s) : scalar_fwd(g, k, t->dtype, s);
 }
 
@@ -92,6 +135,7 @@ extern "C" dcp_status_t dcp_merge_partials(dcp_plan_t* plan, const void* o_part,
   if (!lse) return fail(DCP_ERR_INVALID_ARG, "lse is NULL");
   hipStream_t s = (hipStream_t)stream;
   if ((st = plan->ensure_device(s)) != DCP_OK) return st;
+  ProfScope ps(DCP_K_MERGE, s);
   return stream_merge(plan->d_merge_ptr, plan->d_merge_idx, plan->d_fwd.blk_start, plan->d_fwd.blk_len, plan->n_blocks,
                       plan->block_size, o_part, lse_part, out, o_stride_t, o_stride_h, lse, plan->total_tokens, hq, d,
                       dtype, s);
@@ -107,6 +151,7 @@ extern "C" dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_toke
   if ((st = check_tensor("out", t->out, t->o_stride_t, t->o_stride_h, t->d)) != DCP_OK) return st;
   if ((st = check_tensor("dout", t->dout, t->do_stride_t, t->do_stride_h, t->d)) != DCP_OK) return st;
   if (!delta) return fail(DCP_ERR_INVALID_ARG, "delta is NULL");
+  ProfScope ps(DCP_K_DELTA, (hipStream_t)stream);
   return stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
                       total_tokens, t->hq, t->d, t->dtype, (hipStream_t)stream);
 }
@@ -146,14 +191,17 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
   KTensors k = pack(plan, t);
   float* delta = (float*)workspace;
   k.delta = delta;
-  if ((st = stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
-                         plan->total_tokens, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;
-  if (use_mfma) {
-    if ((st = mfma_bwd_dq(gq, k, s)) != DCP_OK) return st;
-    return mfma_bwd_dkv(gkv, k, s);
+  {
+    ProfScope ps(DCP_K_DELTA, s);
+    if ((st = stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
+                           plan->total_tokens, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;
   }
-  if ((st = scalar_bwd_dq(gq, k, t->dtype, s)) != DCP_OK) return st;
-  return scalar_bwd_dkv(gkv, k, t->dtype, s);
+  {
+    ProfScope ps(DCP_K_DQ, s);
+    if ((st = use_mfma ? mfma_bwd_dq(gq, k, s) : scalar_bwd_dq(gq, k, t->dtype, s)) != DCP_OK) return st;
+  }
+  ProfScope ps(DCP_K_DKV, s);
+  return use_mfma ? mfma_bwd_dkv(gkv, k, s) : scalar_bwd_dkv(gkv, k, t->dtype, s);
 }
 
 extern "C" dcp_status_t dcp_sum_partials(const void* const* parts, int32_t n_parts, int32_t parts_dtype, void* dst,
@@ -166,6 +214,7 @@ extern "C" dcp_status_t dcp_sum_partials(const void* const* parts, int32_t n_par
   if (!dst || !aligned16(dst)) return fail(DCP_ERR_INVALID_ARG, "dst is NULL or misaligned");
   for (int i = 0; i < n_parts; i++)
     if (!parts[i] || !aligned16(parts[i])) return fail(DCP_ERR_INVALID_ARG, "a partial pointer is NULL or misaligned");
+  ProfScope ps(DCP_K_SUM, (hipStream_t)stream);
   return stream_sum(parts, n_parts, parts_dtype, dst, dst_dtype, n_elems, (hipStream_t)stream);
 }
 

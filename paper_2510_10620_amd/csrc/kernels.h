@@ -18,6 +18,15 @@ struct KTensors {
   int32_t use_slots;
 };
 
+// Optional per-kernel event timing (see dcp_profile_enable).
+struct ProfScope {
+  int id;
+  hipStream_t s;
+  hipEvent_t stop = nullptr;
+  ProfScope(int id, hipStream_t s);
+  ~ProfScope();
+};
+
 // scalar fp32-ALU family (any dtype; D in {32, 64, 128})
 bool scalar_supports(int32_t d);
 int scalar_fwd_tile();

@@ -203,26 +203,37 @@ def custom_workload(name: str, lens, block_size: int, hq: int, hkv: int, d: int,
 
 
 def make_tensors(w: Workload, with_dout: bool = True) -> Dict[str, np.ndarray]:
-    """q [T,Hq,D], k, v [T,Hkv,D], dout [T,Hq,D] drawn in fp32 from PCG64(tensor_seed) in that
-    order.  For bf16 workloads the arrays are uint16 bf16 bit patterns (the rounding is done
-    here, once, so every consumer sees the same bits); for f32 they are float32."""
-    rng = np.random.default_rng(w.tensor_seed)
+    """q [T,Hq,D], k, v [T,Hkv,D] ~ N(0,1) * input_scale and dout [T,Hq,D] ~ N(0,1), drawn in fp32.
+    Tensor number i (q, k, v, dout = 0..3) is cut into chunks of whole token rows (about 2^22
+    elements); chunk c is filled from its own generator PCG64(SeedSequence([tensor_seed, i, c])),
+    so the result does not depend on how many threads fill the chunks.  For bf16 workloads the
+    arrays are uint16 bf16 bit patterns (rounded here, once, so every consumer sees the same bits);
+    for f32 they are float32."""
+    from concurrent.futures import ThreadPoolExecutor
     T = w.total_tokens
     out = {}
     shapes = [("q", (T, w.hq, w.d), w.input_scale), ("k", (T, w.hkv, w.d), w.input_scale),
               ("v", (T, w.hkv, w.d), w.input_scale)]
     if with_dout:
         shapes.append(("dout", (T, w.hq, w.d), 1.0))
-    for name, shp, sc in shapes:
-        rows = max(1, (1 << 24) // (shp[1] * shp[2]))
+    jobs = []
+    for ti, (name, shp, sc) in enumerate(shapes):
+        rows = max(1, (1 << 22) // (shp[1] * shp[2]))
         dst = np.empty(shp, dtype=np.uint16 if w.dtype == "bf16" else np.float32)
-        for r0 in range(0, T, rows):
-            r1 = min(T, r0 + rows)
-            x = rng.standard_normal((r1 - r0,) + shp[1:], dtype=np.float32)
-            if sc != 1.0:
-                x *= np.float32(sc)
-            dst[r0:r1] = f32_to_bf16_bits(x) if w.dtype == "bf16" else x
         out[name] = dst
+        for ci, r0 in enumerate(range(0, T, rows)):
+            jobs.append((dst, ti, ci, r0, min(T, r0 + rows), shp, sc))
+
+    def fill(job):
+        dst, ti, ci, r0, r1, shp, sc = job
+        rng = np.random.default_rng([w.tensor_seed, ti, ci])
+        x = rng.standard_normal((r1 - r0,) + shp[1:], dtype=np.float32)
+        if sc != 1.0:
+            x *= np.float32(sc)
+        dst[r0:r1] = f32_to_bf16_bits(x) if w.dtype == "bf16" else x
+
+    with ThreadPoolExecutor(max_workers=min(16, max(1, len(jobs)))) as ex:
+        list(ex.map(fill, jobs))
     return out
 
 

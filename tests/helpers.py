@@ -57,6 +57,32 @@ class GpuRun:
         torch.cuda.synchronize()
         return from_torch(self.out), from_torch(self.lse)
 
+    def forward_only(self):
+        """forward() without copying the results to the host."""
+        P, torch, w = self.P, self.torch, self.w
+        if self.use_slots:
+            if not hasattr(self, "o_part"):
+                self.o_part = torch.full((self.n_slots, w.block_size, w.hq, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+                self.lse_part = torch.full((self.n_slots, w.hq, w.block_size), float("nan"), dtype=torch.float32, device="cuda")
+            P.dcp_block_attn_fwd(self.plan, self.q, self.k, self.v, self.o_part, self.lse_part, w.softmax_scale, self.ranges, self.impl)
+            P.dcp_merge_partials(self.plan, self.o_part, self.lse_part, self.out, self.lse)
+        else:
+            P.dcp_block_attn_fwd(self.plan, self.q, self.k, self.v, self.out, self.lse, w.softmax_scale, self.ranges, self.impl)
+        torch.cuda.synchronize()
+
+    def backward_only(self, out, lse):
+        """backward() on device tensors, results left on the device (dq, dk, dv)."""
+        P, torch, w = self.P, self.torch, self.w
+        T = w.total_tokens
+        self.dq = torch.full((T, w.hq, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+        self.dk = torch.full((T, w.hkv, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+        self.dv = torch.full((T, w.hkv, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
+        nbytes = P.dcp_bwd_workspace_bytes(self.plan, w.hq, w.hkv, w.d, P.DCP_BF16 if w.dtype == "bf16" else P.DCP_F32)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        P.dcp_block_attn_bwd(self.plan, self.q, self.k, self.v, out, lse, self.dout, self.dq, self.dk, self.dv,
+                             w.softmax_scale, ws, self.ranges, self.impl)
+        torch.cuda.synchronize()
+
     def backward(self, out=None, lse=None):
         """Uses the forward's out/lse unless the global ones are passed (device tensors)."""
         P, torch, w = self.P, self.torch, self.w

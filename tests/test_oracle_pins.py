@@ -401,3 +401,23 @@ def test_bf16_rounding_helper_is_nearest_even_and_exact_on_widening():
     ref = torch.from_numpy(x).to(torch.bfloat16)
     assert np.array_equal(bits.view(np.int16), ref.view(torch.int16).numpy())
     assert np.array_equal(W.bf16_bits_to_f64(bits), ref.to(torch.float64).numpy())
+
+
+def test_row_window_matches_full_computation():
+    """The query-row window of the oracle (used to sample full-size batches) agrees with the
+    full computation on its rows, and its dK/dV are complete for keys only the window sees."""
+    spec = W.MaskSpec("lambda", window=30, sink=4)
+    cu, q, k, v, do, table, ranges = small_case(spec, [90, 41], 16, 4, 2, 8, seed=23)
+    vis = Bk.Visibility(cu, 16, table, ranges)
+    O, LSE = A.attention_fwd(q, k, v, cu, vis, 0.3)
+    dq, dk, dv = A.attention_bwd(q, k, v, do, cu, vis, 0.3)
+    rows = {0: (60, 90)}
+    Ow, Lw = A.attention_fwd(q, k, v, cu, vis, 0.3, seqs=[0], rows=rows, row_chunk=7)
+    dqw, dkw, dvw = A.attention_bwd(q, k, v, do, cu, vis, 0.3, seqs=[0], rows=rows, row_chunk=7)
+    np.testing.assert_allclose(Ow[60:90], O[60:90], atol=1e-12)
+    np.testing.assert_allclose(Lw[:, 60:90], LSE[:, 60:90], atol=1e-12)
+    np.testing.assert_allclose(dqw[60:90], dq[60:90], atol=1e-12)
+    assert np.isnan(Ow[:60]).all() and np.isnan(Ow[90:]).all() and np.isnan(dqw[:60]).all()
+    # keys >= 60 are seen only by queries >= 60 (every mask here is causal-bounded)
+    np.testing.assert_allclose(dkw[60:90], dk[60:90], atol=1e-12)
+    np.testing.assert_allclose(dvw[60:90], dv[60:90], atol=1e-12)
