@@ -89,6 +89,22 @@ def cpu_baseline(w, table, q, k, v, do, budget_pairs=6.0e7):
                        f"{pairs} visible pairs x {G} heads x 14*D flops")
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, scaled by a copy of known size), or None if the summary does not list it.  The
+    summary is a measurement of an earlier run of this same command, not of this run."""
+    path = os.path.join(ROOT, "profiles", "bench_config2_hbm_traffic.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 4 and parts[0] == "traffic" and parts[1] == kernel:
+                    return sum(int(float(p.split("=")[1])) for p in parts[2:])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,9 +167,11 @@ def main():
         kern[name] = dict(ms=tot / max(n, 1), launches=n)
     dom = max(("fwd", "dq", "dkv"), key=lambda n: kern[n]["ms"])
     ach = alg[dom] / (kern[dom]["ms"] * 1e-3) / 1e12
-    roofline = dict(kernel={"fwd": "mfma_fwd_kernel", "dq": "mfma_dq_kernel", "dkv": "mfma_dkv_kernel"}[dom],
+    kname = {"fwd": "mfma_fwd_kernel", "dq": "mfma_dq_kernel", "dkv": "mfma_dkv_kernel"}[dom]
+    roofline = dict(kernel=kname,
                     bound="mfma", achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    frac=round(ach / PEAK_BF16_TFLOPS, 4),
+                    traffic=measured_traffic(kname) if args.config == 2 else None,
                     executed_tflops=round(executed[dom] / (kern[dom]["ms"] * 1e-3) / 1e12, 1))
     delta_bytes = T * w.hq * (4 * w.d + 4)
     per_kernel = {n: dict(ms=round(kern[n]["ms"], 4),
@@ -166,6 +184,14 @@ def main():
                  table_rows=int(len(table)), n_seq=int(len(w.cu_seqlens) - 1))
     if not args.no_extra:
         extra["share"] = share_section(torch, P, W, np, steps=max(3, args.steps // 4), warmup=2)
+
+    # one plain copy of known size (256 MiB read + 256 MiB written) through the library's sum
+    # kernel with a single part: the reference dispatch that scales hardware byte counters
+    cal_src = torch.empty(128 << 20, dtype=torch.bfloat16, device="cuda").fill_(1.0)
+    cal_dst = torch.empty_like(cal_src)
+    P.dcp_sum_partials([cal_src], cal_dst)
+    torch.cuda.synchronize()
+    extra["calibration_copy"] = "sum_kernel<bf16,bf16> with 1 part: 268435456 bytes read, 268435456 bytes written"
 
     value = flops / (ms * 1e-3) / 1e12
     line = dict(metric="effective attention TFLOP/s fwd+bwd (unmasked FLOPs) and % of bf16 MFMA peak",
