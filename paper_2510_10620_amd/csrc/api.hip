@@ -152,15 +152,16 @@ extern "C" dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_toke
   if ((st = check_tensor("dout", t->dout, t->do_stride_t, t->do_stride_h, t->d)) != DCP_OK) return st;
   if (!delta) return fail(DCP_ERR_INVALID_ARG, "delta is NULL");
   ProfScope ps(DCP_K_DELTA, (hipStream_t)stream);
-  return stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
-                      total_tokens, t->hq, t->d, t->dtype, (hipStream_t)stream);
+  return stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta, nullptr,
+                      nullptr, total_tokens, t->hq, t->d, t->dtype, (hipStream_t)stream);
 }
 
 extern "C" size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype) {
   (void)hkv; (void)d; (void)dtype;
   if (!plan || hq <= 0) return 0;
-  size_t n = (size_t)hq * (size_t)plan->total_tokens * sizeof(float);  // delta [Hq,T]
-  return (n + 255) & ~(size_t)255;
+  size_t n = (size_t)hq * (size_t)plan->total_tokens * sizeof(float);  // delta [Hq,T], then lse2 [Hq,T]
+  n = (n + 255) & ~(size_t)255;
+  return 2 * n;
 }
 
 extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace,
@@ -190,11 +191,13 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
   if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv)) != DCP_OK) return st;
   KTensors k = pack(plan, t);
   float* delta = (float*)workspace;
+  float* lse2 = (float*)((char*)workspace + need / 2);
   k.delta = delta;
+  k.lse2 = lse2;
   {
     ProfScope ps(DCP_K_DELTA, s);
     if ((st = stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
-                           plan->total_tokens, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;
+                           t->lse, lse2, plan->total_tokens, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;
   }
   {
     ProfScope ps(DCP_K_DQ, s);

@@ -10,6 +10,7 @@ struct KTensors {
   void *out, *dq, *dk, *dv;
   float* lse;              // forward: output; backward: input
   const float* delta;      // backward input [Hq,T]
+  const float* lse2;       // backward input [Hq,T]: max(lse * log2(e), -FLT_MAX), made by the preprocess
   const int32_t* ranges;   // [T,4] or null
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh, dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
   int64_t total_tokens;
@@ -50,7 +51,8 @@ dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, co
                           const float* lse_part, void* out, int64_t o_st, int64_t o_sh, float* lse,
                           int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s);
 dcp_status_t stream_delta(const void* o, int64_t o_st, int64_t o_sh, const void* dout, int64_t do_st, int64_t do_sh,
-                          float* delta, int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s);
+                          float* delta, const float* lse, float* lse2, int64_t total_tokens, int32_t hq, int32_t d,
+                          int32_t dtype, hipStream_t s);
 dcp_status_t stream_sum(const void* const* parts, int32_t n_parts, int32_t parts_dtype, void* dst, int32_t dst_dtype,
                         int64_t n, hipStream_t s);
 

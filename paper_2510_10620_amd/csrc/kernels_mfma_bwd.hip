@@ -15,15 +15,15 @@ static constexpr float kLog2e = 1.44269504088896340736f;
 struct DqState {
   bf16x8 qf[8], dof[8];
   f32x16 dq[4];
-  float lse2, delta;  // lse * log2(e) (+inf when the row saw nothing), delta
+  float lse2, delta;  // lse * log2(e) clamped to a finite value (a row that saw nothing has every score masked), delta
   int qi;
   int4 qr;
   FragAddr fa;
+  TileDma dma;
 };
 
-template <bool MASK>
 __device__ __forceinline__ void dq_subtile(DqState& st, const char* k_lds, const char* v_lds, int kt, int ks32,
-                                           int kind, int c0, int c1, float c_log2, int lane) {
+                                           int kind, int c0, int c1, float c_log2, int lane, bool MASK) {
   const int lh = lane >> 5;
   f32x16 s, dp;
 #pragma unroll
@@ -65,11 +65,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   const int G = t.hq / t.hkv;
   if (!decode_wg(g.n_items, t.hkv, G, &item, &head)) return;
   const int hk = head / G;
-  const WorkItem w = g.items[item];
-  const int qb = g.unit_blk[w.unit];
+  WorkItem w = g.items[item];
+  w.unit = uni(w.unit); w.tile = uni(w.tile);
+  const int qb = uni(g.unit_blk[w.unit]);
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
-  const int blk_start = g.blk_start[qb], blk_len = g.blk_len[qb];
+  const int blk_start = uni(g.blk_start[qb]), blk_len = uni(g.blk_len[qb]);
   const int row0 = w.tile * TM;
   const int n_rows = min(TM, blk_len - row0);
   const int q_lo = blk_start + row0, q_hi = q_lo + n_rows - 1;
@@ -79,6 +80,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
 
   DqState st;
   st.fa.init(lane);
+  st.dma.init(wave, lane);
   const int r = wrow0 + li;
   const bool qv = r < n_rows;
   st.qi = q_lo + min(r, n_rows - 1);
@@ -118,8 +120,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
       st.qf[ks] = as_frag(*(const uint4*)(qp + 16 * ks));
       st.dof[ks] = as_frag(*(const uint4*)(dop + 16 * ks));
     }
-    const float lse = t.lse[(int64_t)head * t.total_tokens + st.qi];
-    st.lse2 = lse == -INFINITY ? INFINITY : lse * kLog2e;
+    st.lse2 = t.lse2[(int64_t)head * t.total_tokens + st.qi];
     st.delta = t.delta[(int64_t)head * t.total_tokens + st.qi];
 #pragma unroll
     for (int dt = 0; dt < 4; dt++)
@@ -133,25 +134,22 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   KvIter it(g, w.unit);
   bool have = it.next(q_hi, rb);
   if (have) {
-    tile_load_async(stage0, kbase, t.k_st, it.ks, it.c1 - 1, wave, lane);
-    tile_load_async(stage0 + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave, lane);
+    st.dma.load(stage0, kbase, t.k_st, it.ks, it.c1 - 1, wave);
+    st.dma.load(stage0 + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
   }
   __syncthreads();
   auto step = [&](const char* cur, char* nxt) {
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
     have = it.next(q_hi, rb);
     if (have) {
-      tile_load_async(nxt, kbase, t.k_st, it.ks, it.c1 - 1, wave, lane);
-      tile_load_async(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave, lane);
+      st.dma.load(nxt, kbase, t.k_st, it.ks, it.c1 - 1, wave);
+      st.dma.load(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
     }
     if (w_rows > 0) {
 #pragma unroll
       for (int kt = 0; kt < 2; kt++) {
         const int cls = classify32(kind, ks + 32 * kt, c1, wq_lo, wq_hi, wrb);
-        if (cls == kFull)
-          dq_subtile<false>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane);
-        else if (cls == kPartial)
-          dq_subtile<true>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane);
+        if (cls != kSkip) dq_subtile(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane, cls == kPartial);
       }
     }
     __syncthreads();
@@ -188,7 +186,7 @@ struct QIter {
   int q0, q1, kind;
   int qs;  // first query of the current tile
   __device__ QIter(const DevGroup& g, int unit, int G_) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind) {
-    e = g.ptr[unit] - 1; e_end = g.ptr[unit + 1]; hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; qs = 0;
+    e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; qs = 0;
   }
   // k_lo: first key of the workgroup's tile.  Under CAUSAL, query tiles that end before k_lo see nothing.
   __device__ bool next(int k_lo) {
@@ -200,7 +198,7 @@ struct QIter {
           e++;
           if (e >= e_end) return false;
           hh = 0;
-          q0 = ent_start[e]; q1 = q0 + ent_len[e]; kind = ent_kind[e];
+          q0 = uni(ent_start[e]); q1 = q0 + uni(ent_len[e]); kind = uni(ent_kind[e]);
           n_t = (q1 - q0 + kTN - 1) / kTN;
           jt0 = kind == 1 ? max(0, (k_lo - q0) / kTN) : 0;
         }
@@ -218,11 +216,11 @@ struct DkvState {
   f32x16 dk[4], dv[4];
   int kj;
   FragAddr fa;
+  TileDma dma;
 };
 
-template <bool MASK>
 __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int qt, int qs32, int q1, int kind,
-                                            int k_end, float c_log2, int lane) {
+                                            int k_end, float c_log2, int lane, bool MASK) {
   const int lh = lane >> 5;
   const char* q_lds = stage;
   const char* do_lds = stage + kTileBytes;
@@ -233,6 +231,30 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
   for (int ksd = 0; ksd < 8; ksd++) {
     s = mfma(frag_rm(q_lds, st.fa, 32 * qt, ksd), st.kf[ksd], s);
     dp = mfma(frag_rm(do_lds, st.fa, 32 * qt, ksd), st.vf[ksd], dp);
+  }
+  if (MASK) {
+    // element r = 4a + b is (query qs32 + 8a + 4 lh + b, key kj); queries past the block end are
+    // clamped duplicates of its last row and must not count
+    const int qb0 = qs32 + 4 * lh;
+    const bool kok = st.kj < k_end;
+    if (kind == 2) {
+      const int4* rg_lds = (const int4*)(stage + kStageRanges) + 32 * qt + 4 * lh;
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int4 rg = rg_lds[8 * (r / 4) + (r % 4)];
+        const int q = qb0 + 8 * (r / 4) + (r % 4);
+        const bool vis = kok & (q < q1) & (((st.kj >= rg.x) & (st.kj < rg.y)) | ((st.kj >= rg.z) & (st.kj < rg.w)));
+        s[r] = vis ? s[r] : -INFINITY;
+      }
+    } else {
+      const int kcmp = kind == 1 ? st.kj : INT32_MIN;   // causal: key <= query
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int q = qb0 + 8 * (r / 4) + (r % 4);
+        const bool vis = kok & (q < q1) & (kcmp <= q);
+        s[r] = vis ? s[r] : -INFINITY;
+      }
+    }
   }
   // rows of the C tile are queries 8a + 4 lh + b: their LSE / delta come from LDS (broadcast reads)
   const float* lse_lds = (const float*)(stage + kStageLse) + 32 * qt + 4 * lh;
@@ -245,19 +267,7 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
 #pragma unroll
     for (int b = 0; b < 4; b++) {
       const int r = 4 * a + b;
-      const float lse2 = lv[b] == -INFINITY ? INFINITY : lv[b] * kLog2e;
-      float x = s[r];
-      if (MASK) {
-        const int q = qs32 + 8 * a + 4 * lh + b;
-        bool vis = q < q1 && st.kj < k_end;
-        if (kind == 1) vis = vis && st.kj <= q;
-        if (kind == 2) {
-          const int4 rg = *(const int4*)(stage + kStageRanges + (32 * qt + 8 * a + 4 * lh + b) * 16);
-          vis = vis && ((st.kj >= rg.x && st.kj < rg.y) || (st.kj >= rg.z && st.kj < rg.w));
-        }
-        if (!vis) x = -INFINITY;
-      }
-      const float p = __builtin_amdgcn_exp2f(fmaf(x, c_log2, -lse2));
+      const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c_log2, -lv[b]));
       s[r] = p;
       dp[r] = p * (dp[r] - dv4[b]);
     }
@@ -281,11 +291,12 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   int item, hk;
   if (!decode_wg(g.n_items, t.hkv, 1, &item, &hk)) return;
   const int G = t.hq / t.hkv;
-  const WorkItem w = g.items[item];
-  const int kb = g.unit_blk[w.unit];
+  WorkItem w = g.items[item];
+  w.unit = uni(w.unit); w.tile = uni(w.tile);
+  const int kb = uni(g.unit_blk[w.unit]);
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
-  const int blk_start = g.blk_start[kb], blk_len = g.blk_len[kb];
+  const int blk_start = uni(g.blk_start[kb]), blk_len = uni(g.blk_len[kb]);
   const int row0 = w.tile * TK;
   const int n_rows = min(TK, blk_len - row0);
   const int k_lo = blk_start + row0, k_end = k_lo + n_rows;
@@ -295,6 +306,7 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
 
   DkvState st;
   st.fa.init(lane);
+  st.dma.init(wave, lane);
   const bool kvalid = wrow0 + li < n_rows;
   st.kj = k_lo + wrow0 + li;                       // may lie past k_end: masked, never stored
   {
@@ -319,11 +331,11 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   auto issue = [&](char* stage) {
     const int head = hk * G + it.hh;
     const int last = it.q1 - 1;
-    tile_load_async(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, t.q_st, it.qs, last, wave, lane);
-    tile_load_async(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, t.do_st, it.qs, last, wave, lane);
+    st.dma.load(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, t.q_st, it.qs, last, wave);
+    st.dma.load(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, t.do_st, it.qs, last, wave);
     const int qrow = min(it.qs + lane, last);
     if (wave == 0)
-      __builtin_amdgcn_global_load_lds((glb_p)(t.lse + (int64_t)head * t.total_tokens + qrow), (lds_p)(stage + kStageLse), 4, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_p)(t.lse2 + (int64_t)head * t.total_tokens + qrow), (lds_p)(stage + kStageLse), 4, 0, 0);
     if (wave == 1)
       __builtin_amdgcn_global_load_lds((glb_p)(t.delta + (int64_t)head * t.total_tokens + qrow), (lds_p)(stage + kStageDelta), 4, 0, 0);
     if (wave == 2 && it.kind == 2)
@@ -345,10 +357,7 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
         int cls = kPartial;
         if (kind == 0) cls = whole ? kFull : kPartial;
         if (kind == 1) cls = min(qs32 + 31, q1 - 1) < wk_lo ? kSkip : ((whole && qs32 >= wk_hi) ? kFull : kPartial);
-        if (cls == kFull)
-          dkv_subtile<false>(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane);
-        else if (cls == kPartial)
-          dkv_subtile<true>(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane);
+        if (cls != kSkip) dkv_subtile(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane, cls == kPartial);
       }
     }
     __syncthreads();

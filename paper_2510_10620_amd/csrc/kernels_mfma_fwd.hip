@@ -11,6 +11,8 @@
 
 namespace dcp {
 
+static constexpr float kLazy = 8.f;  // rescale threshold, log2 units
+
 template <int NQ>
 struct FwdCfg {
   static constexpr int kWaveRows = 32 * NQ;
@@ -25,12 +27,13 @@ struct FwdState {
   int qi[NQ];
   int4 qr[NQ];
   FragAddr fa;
+  TileDma dma;
 };
 
 // One 32-key sub-tile: S^T = K Q^T, mask, online softmax, O^T += V^T P^T.
-template <int NQ, bool MASK>
+template <int NQ>
 __device__ __forceinline__ void fwd_subtile(FwdState<NQ>& st, const char* k_lds, const char* v_lds, int kt, int ks32,
-                                            int kind, int c0, int c1, float c_log2, int lane) {
+                                            int kind, int c0, int c1, float c_log2, int lane, bool MASK) {
   const int lh = lane >> 5;
   f32x16 s[NQ];
 #pragma unroll
@@ -58,14 +61,28 @@ __device__ __forceinline__ void fwd_subtile(FwdState<NQ>& st, const char* k_lds,
   bf16x8 p[NQ][2];
 #pragma unroll
   for (int nq = 0; nq < NQ; nq++) {
-    float mx = s[nq][0];
+    float mx = fmaxf(fmaxf(s[nq][0], s[nq][1]), s[nq][2]);
 #pragma unroll
-    for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[nq][r]);
+    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[nq][r]), s[nq][r + 1]);
+    mx = fmaxf(mx, s[nq][15]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(st.m[nq], mx);
+    // The reference max m is raised only when the tile's max exceeds it by more than 2^kLazy
+    // (in the exp2 domain): until then P = exp2(c (s - m)) stays below 2^kLazy, exact in fp32 and
+    // bf16 range, and the accumulators need no rescaling.  O and l are divided by the same sum at
+    // the end, so the result does not depend on which m was used.
+    const bool raise = (mx - st.m[nq]) * c_log2 > kLazy;   // also true for the first visible key (m = -inf)
+    const float m_new = raise ? mx : st.m[nq];
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((st.m[nq] - m_use) * c_log2);
     const float mc = m_use * c_log2;
+    if (__any(raise)) {
+      const float alpha = raise ? __builtin_amdgcn_exp2f((st.m[nq] - m_use) * c_log2) : 1.f;
+      st.l[nq] *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) st.o[nq][dt][r] *= alpha;
+    }
+    st.m[nq] = m_new;
     float sum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; r++) {
@@ -73,14 +90,7 @@ __device__ __forceinline__ void fwd_subtile(FwdState<NQ>& st, const char* k_lds,
       s[nq][r] = e;
       sum += e;
     }
-    st.l[nq] = st.l[nq] * alpha + sum;
-    st.m[nq] = m_new;
-    if (__any(alpha != 1.f)) {
-#pragma unroll
-      for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) st.o[nq][dt][r] *= alpha;
-    }
+    st.l[nq] += sum;
 #pragma unroll
     for (int c = 0; c < 2; c++) p[nq][c] = pack_frag(s[nq], c);
   }
@@ -107,11 +117,12 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGro
   const int G = t.hq / t.hkv;
   if (!decode_wg(g.n_items, t.hkv, G, &item, &head)) return;
   const int hk = head / G;
-  const WorkItem w = g.items[item];
-  const int qb = g.unit_blk[w.unit];
+  WorkItem w = g.items[item];
+  w.unit = uni(w.unit); w.tile = uni(w.tile);
+  const int qb = uni(g.unit_blk[w.unit]);
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
-  const int blk_start = g.blk_start[qb], blk_len = g.blk_len[qb];
+  const int blk_start = uni(g.blk_start[qb]), blk_len = uni(g.blk_len[qb]);
   const int row0 = w.tile * TM;                       // first row of the tile inside the block
   const int n_rows = min(TM, blk_len - row0);         // valid rows of the tile (>= 1)
   const int q_lo = blk_start + row0, q_hi = q_lo + n_rows - 1;
@@ -121,6 +132,7 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGro
 
   FwdState<NQ> st;
   st.fa.init(lane);
+  st.dma.init(wave, lane);
   bool qv[NQ];
   RangeBounds wrb;
   wrb.init();
@@ -176,8 +188,8 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGro
   KvIter it(g, w.unit);
   bool have = it.next(q_hi, rb);
   if (have) {
-    tile_load_async(stage0, kbase, t.k_st, it.ks, it.c1 - 1, wave, lane);
-    tile_load_async(stage0 + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave, lane);
+    st.dma.load(stage0, kbase, t.k_st, it.ks, it.c1 - 1, wave);
+    st.dma.load(stage0 + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
   }
   __syncthreads();
 
@@ -186,17 +198,14 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGro
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
     have = it.next(q_hi, rb);
     if (have) {
-      tile_load_async(nxt, kbase, t.k_st, it.ks, it.c1 - 1, wave, lane);
-      tile_load_async(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave, lane);
+      st.dma.load(nxt, kbase, t.k_st, it.ks, it.c1 - 1, wave);
+      st.dma.load(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
     }
     if (w_rows > 0) {
 #pragma unroll
       for (int kt = 0; kt < 2; kt++) {
         const int cls = classify32(kind, ks + 32 * kt, c1, wq_lo, wq_hi, wrb);
-        if (cls == kFull)
-          fwd_subtile<NQ, false>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane);
-        else if (cls == kPartial)
-          fwd_subtile<NQ, true>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane);
+        if (cls != kSkip) fwd_subtile<NQ>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane, cls == kPartial);
       }
     }
     __syncthreads();  // the copy into `nxt` has landed (vmcnt) and `cur` may be overwritten

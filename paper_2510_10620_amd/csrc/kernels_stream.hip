@@ -103,7 +103,8 @@ static constexpr int kDeltaTok = 32;
 template <typename T>
 __global__ __launch_bounds__(256) void delta_kernel(const T* __restrict__ o, int64_t o_st, int64_t o_sh,
                                                     const T* __restrict__ dout, int64_t do_st, int64_t do_sh,
-                                                    float* __restrict__ delta, int64_t total_tokens, int32_t hq,
+                                                    float* __restrict__ delta, const float* __restrict__ lse,
+                                                    float* __restrict__ lse2, int64_t total_tokens, int32_t hq,
                                                     int32_t d) {
   extern __shared__ float sm[];  // [hq][kDeltaTok + 1]
   const int64_t t0 = (int64_t)blockIdx.x * kDeltaTok;
@@ -129,20 +130,24 @@ __global__ __launch_bounds__(256) void delta_kernel(const T* __restrict__ o, int
   for (int it = threadIdx.x; it < hq * ntok; it += blockDim.x) {
     const int h = it / ntok, tl = it % ntok;
     delta[(int64_t)h * total_tokens + t0 + tl] = sm[h * (kDeltaTok + 1) + tl];
+    // log-sum-exp in the exp2 domain for the backward kernels; -inf (a row that saw nothing) becomes
+    // the lowest finite float so that (masked score = -inf) - lse2 stays -inf and P = 0
+    if (lse2) lse2[(int64_t)h * total_tokens + t0 + tl] = fmaxf(lse[(int64_t)h * total_tokens + t0 + tl] * 1.44269504088896340736f, -3.402823466e38f);
   }
 }
 
 dcp_status_t stream_delta(const void* o, int64_t o_st, int64_t o_sh, const void* dout, int64_t do_st, int64_t do_sh,
-                          float* delta, int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s) {
+                          float* delta, const float* lse, float* lse2, int64_t total_tokens, int32_t hq, int32_t d,
+                          int32_t dtype, hipStream_t s) {
   if (total_tokens == 0) return DCP_OK;
   dim3 grid((unsigned)((total_tokens + kDeltaTok - 1) / kDeltaTok)), block(256);
   const size_t sm = (size_t)hq * (kDeltaTok + 1) * sizeof(float);
   if (dtype == DCP_BF16)
     hipLaunchKernelGGL(delta_kernel<bf16_t>, grid, block, sm, s, (const bf16_t*)o, o_st, o_sh, (const bf16_t*)dout,
-                       do_st, do_sh, delta, total_tokens, hq, d);
+                       do_st, do_sh, delta, lse, lse2, total_tokens, hq, d);
   else
     hipLaunchKernelGGL(delta_kernel<float>, grid, block, sm, s, (const float*)o, o_st, o_sh, (const float*)dout, do_st,
-                       do_sh, delta, total_tokens, hq, d);
+                       do_sh, delta, lse, lse2, total_tokens, hq, d);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;
 }

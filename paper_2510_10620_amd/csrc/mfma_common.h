@@ -111,25 +111,42 @@ __device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int c) {
 }
 
 // Asynchronous global -> LDS copy of a 64-row tile (rows [row_start, row_start + 64) of a
-// [T, H, 128] bf16 tensor, head already applied to `base`), rows clamped to row_last so every
-// load reads real data.  global_load_lds_dwordx4 writes lane L's 16 bytes at (uniform LDS base)
-// + 16 L, so one wave instruction fills 4 consecutive tile rows; the swizzle is applied on the
-// global side: the lane that fills physical chunk p of a row fetches logical chunk p ^ swz(row).
-// Each of the 4 waves issues 4 of the 16 instructions of a tile.  Completion is tracked by
-// vmcnt; the data is visible to other waves after s_waitcnt vmcnt(0) + barrier.
-__device__ __forceinline__ void tile_load_async(char* tile, const bf16_t* base, int64_t stride_t, int row_start,
-                                                int row_last, int wave, int lane) {
-  typedef __attribute__((address_space(3))) void* lds_p;
-  typedef __attribute__((address_space(1))) const void* glb_p;
+// [T, H, 128] bf16 tensor, head already applied to `base`).  global_load_lds_dwordx4 writes lane
+// L's 16 bytes at (uniform LDS base) + 16 L, so one wave instruction fills 4 consecutive tile rows;
+// the swizzle is applied on the global side: the lane that fills physical chunk p of a row fetches
+// logical chunk p ^ swz(row).  Each of the 4 waves issues 4 of the 16 instructions of a tile.
+// Completion is tracked by vmcnt; the data is visible to other waves after s_waitcnt vmcnt(0) +
+// barrier.  The lane-dependent byte offsets are computed once (TileDma::init); per tile only the
+// uniform base moves.  A tile that runs past row_last (ragged end) clamps its rows so that every
+// load reads real data.
+struct TileDma {
+  int row[4];    // tile row this lane fetches in instruction u
+  int chunk[4];  // byte offset of its 16-byte chunk inside the row
+  __device__ __forceinline__ void init(int wave, int lane) {
 #pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int n = wave * 4 + u;
-    const int row = 4 * n + (lane >> 4);
-    const int c16 = (lane & 15) ^ swz(row);
-    const int tok = min(row_start + row, row_last);
-    __builtin_amdgcn_global_load_lds((glb_p)(base + (int64_t)tok * stride_t + c16 * 8), (lds_p)(tile + n * 1024), 16, 0, 0);
+    for (int u = 0; u < 4; u++) {
+      row[u] = 4 * (wave * 4 + u) + (lane >> 4);
+      chunk[u] = ((lane & 15) ^ swz(row[u])) * 16;
+    }
   }
-}
+  __device__ __forceinline__ void load(char* tile, const bf16_t* base, int64_t stride_t, int row_start, int row_last,
+                                       int wave) const {
+    typedef __attribute__((address_space(3))) void* lds_p;
+    typedef __attribute__((address_space(1))) const void* glb_p;
+    const char* b = (const char*)(base + (int64_t)row_start * stride_t);   // uniform
+    const int sb = (int)stride_t * 2;
+    if (row_start + kTN - 1 <= row_last) {
+#pragma unroll
+      for (int u = 0; u < 4; u++)
+        __builtin_amdgcn_global_load_lds((glb_p)(b + (unsigned)(row[u] * sb + chunk[u])), (lds_p)(tile + (wave * 4 + u) * 1024), 16, 0, 0);
+    } else {
+      const int lim = row_last - row_start;
+#pragma unroll
+      for (int u = 0; u < 4; u++)
+        __builtin_amdgcn_global_load_lds((glb_p)(b + (unsigned)(min(row[u], lim) * sb + chunk[u])), (lds_p)(tile + (wave * 4 + u) * 1024), 16, 0, 0);
+    }
+  }
+};
 
 // Two half-open key ranges of one query row, clipped to a KV block.
 struct RowRanges {
@@ -217,7 +234,7 @@ struct KvIter {
   int c0, c1, kind;
   int ks;  // first key of the current tile
   __device__ KvIter(const DevGroup& g, int unit) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind) {
-    e = g.ptr[unit] - 1; e_end = g.ptr[unit + 1]; jt = 0; n_t = 0; c0 = c1 = kind = 0; ks = 0;
+    e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); jt = 0; n_t = 0; c0 = c1 = kind = 0; ks = 0;
   }
   // Advances to the next tile some row of [.., q_hi] may see; false when the unit is done.
   __device__ bool next(int q_hi, const RangeBounds& rb) {
@@ -226,7 +243,7 @@ struct KvIter {
       if (jt >= n_t) {
         e++;
         if (e >= e_end) return false;
-        c0 = ent_start[e]; c1 = c0 + ent_len[e]; kind = ent_kind[e];
+        c0 = uni(ent_start[e]); c1 = c0 + uni(ent_len[e]); kind = uni(ent_kind[e]);
         n_t = (c1 - c0 + kTN - 1) / kTN;
         if (kind == 1) n_t = min(n_t, max(0, (q_hi - c0) / kTN + 1));  // tiles starting after q_hi are empty
         jt = -1;
