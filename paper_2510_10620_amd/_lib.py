@@ -4,7 +4,7 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libdcp_attn.so")
+LIB_PATH = os.environ.get("DCP_LIB_PATH") or os.path.join(HERE, "libdcp_attn.so")   # DCP_LIB_PATH: load another build of the same library
 
 i32p = ctypes.POINTER(ctypes.c_int32)
 i64p = ctypes.POINTER(ctypes.c_int64)

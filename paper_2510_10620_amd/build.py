@@ -47,6 +47,24 @@ def _compile(src, force):
     return obj, True
 
 
+def build_variant(out_path, defines):
+    """Builds the library with extra -D flags into another file (for kernel experiments)."""
+    import tempfile
+    tmp = tempfile.mkdtemp(prefix="dcp_variant_")
+    objs = []
+    for src in sources():
+        obj = os.path.join(tmp, src + ".o")
+        cmd = [HIPCC] + COMMON + ["-D" + d for d in defines] + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(r.stderr)
+        objs.append(obj)
+    r = subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out_path] + objs, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(r.stderr)
+    return out_path
+
+
 def build(force=False, verbose=True):
     os.makedirs(BUILD, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(sources()))) as ex:

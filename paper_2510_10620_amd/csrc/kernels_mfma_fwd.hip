@@ -13,10 +13,15 @@ namespace dcp {
 
 static constexpr float kLazy = 8.f;  // rescale threshold, log2 units
 
+#ifndef DCP_FWD_NW
+#define DCP_FWD_NW 4
+#endif
+static constexpr int kFwdWaves = DCP_FWD_NW;   // waves per workgroup (4 or 8)
+
 template <int NQ>
 struct FwdCfg {
   static constexpr int kWaveRows = 32 * NQ;
-  static constexpr int kTileM = 4 * kWaveRows;
+  static constexpr int kTileM = kFwdWaves * kWaveRows;
 };
 
 template <int NQ>
@@ -27,7 +32,7 @@ struct FwdState {
   int qi[NQ];
   int4 qr[NQ];
   FragAddr fa;
-  TileDma dma;
+  TileDmaT<16 / kFwdWaves> dma;
 };
 
 // One 32-key sub-tile: S^T = K Q^T, mask, online softmax, O^T += V^T P^T.
@@ -104,14 +109,82 @@ __device__ __forceinline__ void fwd_subtile(FwdState<NQ>& st, const char* k_lds,
     }
 }
 
+// A whole 64-key tile every pair of which is visible to the wave: the two 32-key score tiles are
+// two independent MFMA chains, and the max / rescale bookkeeping is done once for 64 keys.
 template <int NQ>
-__global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGroup g, KTensors t) {
+__device__ __forceinline__ void fwd_tile64(FwdState<NQ>& st, const char* k_lds, const char* v_lds, float c_log2) {
+  f32x16 s[2][NQ];
+#pragma unroll
+  for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+    for (int nq = 0; nq < NQ; nq++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) s[kt][nq][r] = 0.f;
+#pragma unroll
+  for (int ksd = 0; ksd < 8; ksd++)
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++) {
+      const bf16x8 a = frag_rm(k_lds, st.fa, 32 * kt, ksd);
+#pragma unroll
+      for (int nq = 0; nq < NQ; nq++) s[kt][nq] = mfma(a, st.qf[nq][ksd], s[kt][nq]);
+    }
+  bf16x8 p[2][NQ][2];
+#pragma unroll
+  for (int nq = 0; nq < NQ; nq++) {
+    float mx = fmaxf(fmaxf(s[0][nq][0], s[0][nq][1]), s[1][nq][0]);
+    mx = fmaxf(mx, s[1][nq][1]);
+#pragma unroll
+    for (int r = 2; r < 16; r += 2) {
+      mx = fmaxf(fmaxf(mx, s[0][nq][r]), s[0][nq][r + 1]);
+      mx = fmaxf(fmaxf(mx, s[1][nq][r]), s[1][nq][r + 1]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const bool raise = (mx - st.m[nq]) * c_log2 > kLazy;
+    const float m_new = raise ? mx : st.m[nq];
+    const float mc = m_new * c_log2;               // finite: a full tile has a finite max
+    if (__any(raise)) {
+      const float alpha = raise ? __builtin_amdgcn_exp2f((st.m[nq] - m_new) * c_log2) : 1.f;
+      st.l[nq] *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) st.o[nq][dt][r] *= alpha;
+    }
+    st.m[nq] = m_new;
+    float sum0 = 0.f, sum1 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const float e0 = __builtin_amdgcn_exp2f(fmaf(s[0][nq][r], c_log2, -mc));
+      const float e1 = __builtin_amdgcn_exp2f(fmaf(s[1][nq][r], c_log2, -mc));
+      s[0][nq][r] = e0; s[1][nq][r] = e1;
+      sum0 += e0; sum1 += e1;
+    }
+    st.l[nq] += sum0 + sum1;
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+      for (int c = 0; c < 2; c++) p[kt][nq][c] = pack_frag(s[kt][nq], c);
+  }
+#pragma unroll
+  for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+    for (int c = 0; c < 2; c++)
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) {
+        const bf16x8 a = frag_tr(v_lds, st.fa, 32 * kt + 16 * c, dt);
+#pragma unroll
+        for (int nq = 0; nq < NQ; nq++) st.o[nq][dt] = mfma(a, p[kt][nq][c], st.o[nq][dt]);
+      }
+}
+
+template <int NQ>
+__global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGroup g, KTensors t) {
   constexpr int WR = FwdCfg<NQ>::kWaveRows, TM = FwdCfg<NQ>::kTileM;
   // two stages, each [K tile | V tile]; separate arrays so that the asynchronous copy into one is
   // known not to alias the reads from the other
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
-  __shared__ int wg_bounds[4][8];
+  __shared__ int wg_bounds[kFwdWaves][8];
 
   int item, head;
   const int G = t.hq / t.hkv;
@@ -156,7 +229,7 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGro
     }
     __syncthreads();
     rb.init();
-    for (int x = 0; x < 4; x++) {
+    for (int x = 0; x < kFwdWaves; x++) {
       rb.lo_min[0] = min(rb.lo_min[0], wg_bounds[x][0]); rb.lo_max[0] = max(rb.lo_max[0], wg_bounds[x][1]);
       rb.hi_min[0] = min(rb.hi_min[0], wg_bounds[x][2]); rb.hi_max[0] = max(rb.hi_max[0], wg_bounds[x][3]);
       rb.lo_min[1] = min(rb.lo_min[1], wg_bounds[x][4]); rb.lo_max[1] = max(rb.lo_max[1], wg_bounds[x][5]);
@@ -202,10 +275,12 @@ __global__ __launch_bounds__(256, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGro
       st.dma.load(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
     }
     if (w_rows > 0) {
-#pragma unroll
-      for (int kt = 0; kt < 2; kt++) {
-        const int cls = classify32(kind, ks + 32 * kt, c1, wq_lo, wq_hi, wrb);
-        if (cls != kSkip) fwd_subtile<NQ>(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane, cls == kPartial);
+      const int cls0 = classify32(kind, ks, c1, wq_lo, wq_hi, wrb), cls1 = classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb);
+      if (cls0 == kFull && cls1 == kFull) {
+        fwd_tile64<NQ>(st, cur, cur + kTileBytes, c_log2);
+      } else {
+        if (cls0 != kSkip) fwd_subtile<NQ>(st, cur, cur + kTileBytes, 0, ks, kind, c0, c1, c_log2, lane, cls0 == kPartial);
+        if (cls1 != kSkip) fwd_subtile<NQ>(st, cur, cur + kTileBytes, 1, ks + 32, kind, c0, c1, c_log2, lane, cls1 == kPartial);
       }
     }
     __syncthreads();  // the copy into `nxt` has landed (vmcnt) and `cur` may be overwritten
@@ -256,7 +331,7 @@ dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
   const int total = g.n_items * t.hq;
   const int per_xcd = (total + 7) / 8;
-  hipLaunchKernelGGL(mfma_fwd_kernel<DCP_FWD_NQ>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  hipLaunchKernelGGL(mfma_fwd_kernel<DCP_FWD_NQ>, dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;
 }

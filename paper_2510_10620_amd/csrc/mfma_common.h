@@ -119,13 +119,14 @@ __device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int c) {
 // barrier.  The lane-dependent byte offsets are computed once (TileDma::init); per tile only the
 // uniform base moves.  A tile that runs past row_last (ragged end) clamps its rows so that every
 // load reads real data.
-struct TileDma {
-  int row[4];    // tile row this lane fetches in instruction u
-  int chunk[4];  // byte offset of its 16-byte chunk inside the row
+template <int PW>
+struct TileDmaT {
+  int row[PW];    // tile row this lane fetches in instruction u
+  int chunk[PW];  // byte offset of its 16-byte chunk inside the row
   __device__ __forceinline__ void init(int wave, int lane) {
 #pragma unroll
-    for (int u = 0; u < 4; u++) {
-      row[u] = 4 * (wave * 4 + u) + (lane >> 4);
+    for (int u = 0; u < PW; u++) {
+      row[u] = 4 * (wave * PW + u) + (lane >> 4);
       chunk[u] = ((lane & 15) ^ swz(row[u])) * 16;
     }
   }
@@ -137,16 +138,18 @@ struct TileDma {
     const int sb = (int)stride_t * 2;
     if (row_start + kTN - 1 <= row_last) {
 #pragma unroll
-      for (int u = 0; u < 4; u++)
-        __builtin_amdgcn_global_load_lds((glb_p)(b + (unsigned)(row[u] * sb + chunk[u])), (lds_p)(tile + (wave * 4 + u) * 1024), 16, 0, 0);
+      for (int u = 0; u < PW; u++)
+        __builtin_amdgcn_global_load_lds((glb_p)(b + (unsigned)(row[u] * sb + chunk[u])), (lds_p)(tile + (wave * PW + u) * 1024), 16, 0, 0);
     } else {
       const int lim = row_last - row_start;
 #pragma unroll
-      for (int u = 0; u < 4; u++)
-        __builtin_amdgcn_global_load_lds((glb_p)(b + (unsigned)(min(row[u], lim) * sb + chunk[u])), (lds_p)(tile + (wave * 4 + u) * 1024), 16, 0, 0);
+      for (int u = 0; u < PW; u++)
+        __builtin_amdgcn_global_load_lds((glb_p)(b + (unsigned)(min(row[u], lim) * sb + chunk[u])), (lds_p)(tile + (wave * PW + u) * 1024), 16, 0, 0);
     }
   }
 };
+
+typedef TileDmaT<4> TileDma;   // 4 waves per workgroup
 
 // Two half-open key ranges of one query row, clipped to a KV block.
 struct RowRanges {
