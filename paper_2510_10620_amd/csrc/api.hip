@@ -87,7 +87,8 @@ static KTensors pack(const dcp_plan_t* plan, const dcp_tensors_t* t) {
   KTensors k{};
   k.q = t->q; k.k = t->k; k.v = t->v; k.dout = t->dout; k.out_in = t->out;
   k.out = t->out; k.dq = t->dq; k.dk = t->dk; k.dv = t->dv;
-  k.lse = t->lse; k.delta = nullptr; k.ranges = t->attn_ranges;
+  k.lse = t->lse; k.delta = nullptr;
+  k.ranges = plan->has_ranges ? t->attn_ranges : nullptr;   // kernels skip all range work when no row is RANGES
   k.q_st = t->q_stride_t; k.q_sh = t->q_stride_h; k.k_st = t->k_stride_t; k.k_sh = t->k_stride_h;
   k.v_st = t->v_stride_t; k.v_sh = t->v_stride_h; k.o_st = t->o_stride_t; k.o_sh = t->o_stride_h;
   k.do_st = t->do_stride_t; k.do_sh = t->do_stride_h; k.dq_st = t->dq_stride_t; k.dq_sh = t->dq_stride_h;

@@ -283,7 +283,10 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
   }
 }
 
-__global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t) {
+#ifndef DCP_DKV_OCC
+#define DCP_DKV_OCC 1
+#endif
+__global__ __launch_bounds__(256, DCP_DKV_OCC) void mfma_dkv_kernel(DevGroup g, KTensors t) {
   constexpr int TK = 128;
   __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];
   __shared__ __attribute__((aligned(1024))) char stage1[kStageBytes];
