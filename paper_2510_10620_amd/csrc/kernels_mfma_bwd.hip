@@ -19,7 +19,7 @@ struct DqState {
   int qi;
   int4 qr;
   FragAddr fa;
-  TileDma dma;
+  TileDma dmak, dmav;
 };
 
 __device__ __forceinline__ void dq_subtile(DqState& st, const char* k_lds, const char* v_lds, int kt, int ks32,
@@ -80,7 +80,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
 
   DqState st;
   st.fa.init(lane);
-  st.dma.init(wave, lane);
+  st.dmak.init(wave, lane, t.k_st);
+  st.dmav.init(wave, lane, t.v_st);
   const int r = wrow0 + li;
   const bool qv = r < n_rows;
   st.qi = q_lo + min(r, n_rows - 1);
@@ -134,16 +135,17 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   KvIter it(g, w.unit);
   bool have = it.next(q_hi, rb);
   if (have) {
-    st.dma.load(stage0, kbase, t.k_st, it.ks, it.c1 - 1, wave);
-    st.dma.load(stage0 + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
+    st.dmak.load(stage0, kbase, it.ks, it.c1 - 1, wave);
+    st.dmav.load(stage0 + kTileBytes, vbase, it.ks, it.c1 - 1, wave);
   }
+  DCP_WAIT_VMCNT(0);
   __syncthreads();
   auto step = [&](const char* cur, char* nxt) {
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
     have = it.next(q_hi, rb);
     if (have) {
-      st.dma.load(nxt, kbase, t.k_st, it.ks, it.c1 - 1, wave);
-      st.dma.load(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
+      st.dmak.load(nxt, kbase, it.ks, it.c1 - 1, wave);
+      st.dmav.load(nxt + kTileBytes, vbase, it.ks, it.c1 - 1, wave);
     }
     if (w_rows > 0) {
 #pragma unroll
@@ -152,6 +154,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
         if (cls != kSkip) dq_subtile(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane, cls == kPartial);
       }
     }
+    DCP_WAIT_VMCNT(0);
     __syncthreads();
   };
   while (have) {
@@ -216,7 +219,7 @@ struct DkvState {
   f32x16 dk[4], dv[4];
   int kj;
   FragAddr fa;
-  TileDma dma;
+  TileDma dmaq, dmao;
 };
 
 __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int qt, int qs32, int q1, int kind,
@@ -283,10 +286,7 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
   }
 }
 
-#ifndef DCP_DKV_OCC
-#define DCP_DKV_OCC 1
-#endif
-__global__ __launch_bounds__(256, DCP_DKV_OCC) void mfma_dkv_kernel(DevGroup g, KTensors t) {
+__global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t) {
   constexpr int TK = 128;
   __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];
   __shared__ __attribute__((aligned(1024))) char stage1[kStageBytes];
@@ -309,7 +309,8 @@ __global__ __launch_bounds__(256, DCP_DKV_OCC) void mfma_dkv_kernel(DevGroup g, 
 
   DkvState st;
   st.fa.init(lane);
-  st.dma.init(wave, lane);
+  st.dmaq.init(wave, lane, t.q_st);
+  st.dmao.init(wave, lane, t.do_st);
   const bool kvalid = wrow0 + li < n_rows;
   st.kj = k_lo + wrow0 + li;                       // may lie past k_end: masked, never stored
   {
@@ -334,8 +335,8 @@ __global__ __launch_bounds__(256, DCP_DKV_OCC) void mfma_dkv_kernel(DevGroup g, 
   auto issue = [&](char* stage) {
     const int head = hk * G + it.hh;
     const int last = it.q1 - 1;
-    st.dma.load(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, t.q_st, it.qs, last, wave);
-    st.dma.load(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, t.do_st, it.qs, last, wave);
+    st.dmaq.load(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, it.qs, last, wave);
+    st.dmao.load(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, it.qs, last, wave);
     const int qrow = min(it.qs + lane, last);
     if (wave == 0)
       __builtin_amdgcn_global_load_lds((glb_p)(t.lse2 + (int64_t)head * t.total_tokens + qrow), (lds_p)(stage + kStageLse), 4, 0, 0);
@@ -346,6 +347,7 @@ __global__ __launch_bounds__(256, DCP_DKV_OCC) void mfma_dkv_kernel(DevGroup g, 
   };
   bool have = it.next(k_lo);
   if (have) issue(stage0);
+  DCP_WAIT_VMCNT(0);
   __syncthreads();
   auto step = [&](const char* cur, char* nxt) {
     const int qs = it.qs, q1 = it.q1, kind = it.kind;
@@ -363,6 +365,7 @@ __global__ __launch_bounds__(256, DCP_DKV_OCC) void mfma_dkv_kernel(DevGroup g, 
         if (cls != kSkip) dkv_subtile(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane, cls == kPartial);
       }
     }
+    DCP_WAIT_VMCNT(0);
     __syncthreads();
   };
   while (have) {

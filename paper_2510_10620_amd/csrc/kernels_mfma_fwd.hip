@@ -6,7 +6,8 @@
 // the only cross-lane step is one exchange between the two wave halves per 32 keys, and P^T in the
 // MFMA accumulator layout is directly the B operand of O^T += V^T P^T.  K and V tiles are copied
 // global -> LDS asynchronously one tile ahead into the other of two buffers; V^T fragments come
-// from transposing LDS reads.
+// from transposing LDS reads.  A 64-key tile that is fully visible to the wave takes a path with two
+// independent score chains; tiles on a mask edge are handled per 32 keys with the per-element test.
 #include "mfma_common.h"
 
 namespace dcp {
@@ -32,7 +33,7 @@ struct FwdState {
   int qi[NQ];
   int4 qr[NQ];
   FragAddr fa;
-  TileDmaT<16 / kFwdWaves> dma;
+  TileDmaT<16 / kFwdWaves> dmak, dmav;
 };
 
 // One 32-key sub-tile: S^T = K Q^T, mask, online softmax, O^T += V^T P^T.
@@ -180,8 +181,7 @@ __device__ __forceinline__ void fwd_tile64(FwdState<NQ>& st, const char* k_lds, 
 template <int NQ>
 __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGroup g, KTensors t) {
   constexpr int WR = FwdCfg<NQ>::kWaveRows, TM = FwdCfg<NQ>::kTileM;
-  // two stages, each [K tile | V tile]; separate arrays so that the asynchronous copy into one is
-  // known not to alias the reads from the other
+  // two stages, each [K tile | V tile]
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
   __shared__ int wg_bounds[kFwdWaves][8];
@@ -205,7 +205,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
 
   FwdState<NQ> st;
   st.fa.init(lane);
-  st.dma.init(wave, lane);
+  st.dmak.init(wave, lane, t.k_st);
+  st.dmav.init(wave, lane, t.v_st);
   bool qv[NQ];
   RangeBounds wrb;
   wrb.init();
@@ -261,9 +262,10 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
   KvIter it(g, w.unit);
   bool have = it.next(q_hi, rb);
   if (have) {
-    st.dma.load(stage0, kbase, t.k_st, it.ks, it.c1 - 1, wave);
-    st.dma.load(stage0 + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
+    st.dmak.load(stage0, kbase, it.ks, it.c1 - 1, wave);
+    st.dmav.load(stage0 + kTileBytes, vbase, it.ks, it.c1 - 1, wave);
   }
+  DCP_WAIT_VMCNT(0);
   __syncthreads();
 
   // one pipeline step: prefetch the next tile into `nxt`, compute the current one from `cur`
@@ -271,8 +273,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
     have = it.next(q_hi, rb);
     if (have) {
-      st.dma.load(nxt, kbase, t.k_st, it.ks, it.c1 - 1, wave);
-      st.dma.load(nxt + kTileBytes, vbase, t.v_st, it.ks, it.c1 - 1, wave);
+      st.dmak.load(nxt, kbase, it.ks, it.c1 - 1, wave);
+      st.dmav.load(nxt + kTileBytes, vbase, it.ks, it.c1 - 1, wave);
     }
     if (w_rows > 0) {
       const int cls0 = classify32(kind, ks, c1, wq_lo, wq_hi, wrb), cls1 = classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb);
@@ -283,7 +285,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
         if (cls1 != kSkip) fwd_subtile<NQ>(st, cur, cur + kTileBytes, 1, ks + 32, kind, c0, c1, c_log2, lane, cls1 == kPartial);
       }
     }
-    __syncthreads();  // the copy into `nxt` has landed (vmcnt) and `cur` may be overwritten
+    DCP_WAIT_VMCNT(0);
+    __syncthreads();  // the copy into `nxt` has landed and `cur` may be overwritten
   };
   while (have) {
     step(stage0, stage1);

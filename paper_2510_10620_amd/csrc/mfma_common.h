@@ -112,39 +112,52 @@ __device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int c) {
 
 // Asynchronous global -> LDS copy of a 64-row tile (rows [row_start, row_start + 64) of a
 // [T, H, 128] bf16 tensor, head already applied to `base`).  global_load_lds_dwordx4 writes lane
-// L's 16 bytes at (uniform LDS base) + 16 L, so one wave instruction fills 4 consecutive tile rows;
-// the swizzle is applied on the global side: the lane that fills physical chunk p of a row fetches
-// logical chunk p ^ swz(row).  Each of the 4 waves issues 4 of the 16 instructions of a tile.
-// Completion is tracked by vmcnt; the data is visible to other waves after s_waitcnt vmcnt(0) +
-// barrier.  The lane-dependent byte offsets are computed once (TileDma::init); per tile only the
-// uniform base moves.  A tile that runs past row_last (ragged end) clamps its rows so that every
-// load reads real data.
+// L's 16 bytes at (wave-uniform LDS address in M0) + 16 L, so one wave instruction fills 4
+// consecutive tile rows; the swizzle is applied on the global side: the lane that fills physical
+// chunk p of a row fetches logical chunk p ^ swz(row).  Each of the workgroup's waves issues
+// PW = 16 / (waves per workgroup) of the 16 instructions of a tile.
+//
+// The copy is issued from inline assembly in the (scalar base + 32-bit lane offset) form: the
+// lane offsets are computed once per kernel, the base moves on the scalar unit, so a tile costs
+// no vector-ALU work.  The compiler does not see these copies: the caller must execute
+// DCP_WAIT_VMCNT(0) before the barrier that publishes the tile.  A tile that runs past row_last
+// (ragged end) clamps its rows so that every load reads real data.
+__device__ __forceinline__ void dma16(unsigned voffset, const void* sbase, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voffset), "s"(sbase), "s"(lds) : "memory");
+}
+// s_waitcnt vmcnt(N) only (expcnt and lgkmcnt left at their maxima)
+#define DCP_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N)&15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
+
+__device__ __forceinline__ unsigned lds_addr(const void* p) { return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)p; }
+
 template <int PW>
 struct TileDmaT {
-  int row[PW];    // tile row this lane fetches in instruction u
-  int chunk[PW];  // byte offset of its 16-byte chunk inside the row
-  __device__ __forceinline__ void init(int wave, int lane) {
+  int row[PW];        // tile row this lane fetches in instruction u
+  int chunk[PW];      // byte offset of its 16-byte chunk inside the row
+  unsigned off[PW];   // row * stride + chunk, bytes
+  int sb;             // row stride, bytes
+  __device__ __forceinline__ void init(int wave, int lane, int64_t stride_t) {
+    sb = (int)stride_t * 2;
 #pragma unroll
     for (int u = 0; u < PW; u++) {
       row[u] = 4 * (wave * PW + u) + (lane >> 4);
       chunk[u] = ((lane & 15) ^ swz(row[u])) * 16;
+      off[u] = (unsigned)(row[u] * sb + chunk[u]);
     }
   }
-  __device__ __forceinline__ void load(char* tile, const bf16_t* base, int64_t stride_t, int row_start, int row_last,
-                                       int wave) const {
-    typedef __attribute__((address_space(3))) void* lds_p;
-    typedef __attribute__((address_space(1))) const void* glb_p;
-    const char* b = (const char*)(base + (int64_t)row_start * stride_t);   // uniform
-    const int sb = (int)stride_t * 2;
+  __device__ __forceinline__ void load(char* tile, const bf16_t* base, int row_start, int row_last, int wave) const {
+    // wave-uniform by construction; readfirstlane makes it provably so (it must live in SGPRs)
+    const uint64_t bv = (uint64_t)((const char*)base + (int64_t)row_start * sb);
+    const void* b = (const void*)(((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(bv >> 32)) << 32) |
+                                  (unsigned)__builtin_amdgcn_readfirstlane((int)bv));
+    const unsigned l0 = lds_addr(tile) + wave * PW * 1024;
     if (row_start + kTN - 1 <= row_last) {
 #pragma unroll
-      for (int u = 0; u < PW; u++)
-        __builtin_amdgcn_global_load_lds((glb_p)(b + (unsigned)(row[u] * sb + chunk[u])), (lds_p)(tile + (wave * PW + u) * 1024), 16, 0, 0);
+      for (int u = 0; u < PW; u++) dma16(off[u], b, l0 + u * 1024);
     } else {
       const int lim = row_last - row_start;
 #pragma unroll
-      for (int u = 0; u < PW; u++)
-        __builtin_amdgcn_global_load_lds((glb_p)(b + (unsigned)(min(row[u], lim) * sb + chunk[u])), (lds_p)(tile + (wave * PW + u) * 1024), 16, 0, 0);
+      for (int u = 0; u < PW; u++) dma16((unsigned)(min(row[u], lim) * sb + chunk[u]), b, l0 + u * 1024);
     }
   }
 };
