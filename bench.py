@@ -46,7 +46,7 @@ def time_steps(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
-def cpu_baseline(w, table, q, k, v, do, budget_pairs=6.0e7):
+def cpu_baseline(w, table, q, k, v, do, budget_pairs=3.0e8):
     """The oracle as it stands, timed on the first sequences of the batch (until their dense
     L^2 reaches the budget) for the 4 query heads of KV group 0, forward + backward."""
     import numpy as np

@@ -47,14 +47,14 @@ def _compile(src, force):
     return obj, True
 
 
-def build_variant(out_path, defines):
+def build_variant(out_path, defines, extra_flags=()):
     """Builds the library with extra -D flags into another file (for kernel experiments)."""
     import tempfile
     tmp = tempfile.mkdtemp(prefix="dcp_variant_")
     objs = []
     for src in sources():
         obj = os.path.join(tmp, src + ".o")
-        cmd = [HIPCC] + COMMON + ["-D" + d for d in defines] + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC] + COMMON + list(extra_flags) + ["-D" + d for d in defines] + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(r.stderr)
