@@ -230,11 +230,47 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
   f32x16 s, dp;
 #pragma unroll
   for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+  // operand fragments are requested four k-steps ahead of the MFMAs that use them: one exposed LDS round
+  // trip per sub-tile, not one per k-step (left alone, the compiler reuses two registers and waits for every pair)
+  bf16x8 qa[8], da[8];
+  // rows of the C tile are queries 8a + 4 lh + b: their LSE / delta come from LDS (broadcast reads), requested
+  // first so that nothing queued later stands between them and the exponentials
+  const float* lse_lds = (const float*)(stage + kStageLse) + 32 * qt + 4 * lh;
+  const float* dl_lds = (const float*)(stage + kStageDelta) + 32 * qt + 4 * lh;
+  float4 l4[4], d4[4];
+#pragma unroll
+  for (int a = 0; a < 4; a++) {
+    l4[a] = *(const float4*)(lse_lds + 8 * a);
+    d4[a] = *(const float4*)(dl_lds + 8 * a);
+  }
+#pragma unroll
+  for (int ksd = 0; ksd < 4; ksd++) {
+    qa[ksd] = frag_rm(q_lds, st.fa, 32 * qt, ksd);
+    da[ksd] = frag_rm(do_lds, st.fa, 32 * qt, ksd);
+  }
+  // transposed operands of the second half (dO^T, Q^T; two groups of 16 queries): the first group is requested
+  // under the score MFMAs, the second under the exponentials
+  bf16x8 dot[2][4], qt_[2][4];
 #pragma unroll
   for (int ksd = 0; ksd < 8; ksd++) {
-    s = mfma(frag_rm(q_lds, st.fa, 32 * qt, ksd), st.kf[ksd], s);
-    dp = mfma(frag_rm(do_lds, st.fa, 32 * qt, ksd), st.vf[ksd], dp);
+    __builtin_amdgcn_sched_barrier(0);
+    if (ksd + 4 < 8) {
+      qa[ksd + 4] = frag_rm(q_lds, st.fa, 32 * qt, ksd + 4);
+      da[ksd + 4] = frag_rm(do_lds, st.fa, 32 * qt, ksd + 4);
+    } else {
+      dot[0][ksd - 4] = frag_tr(do_lds, st.fa, 32 * qt, ksd - 4);
+      qt_[0][ksd - 4] = frag_tr(q_lds, st.fa, 32 * qt, ksd - 4);
+    }
+    s = mfma(qa[ksd], st.kf[ksd], s);
+    dp = mfma(da[ksd], st.vf[ksd], dp);
   }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++) {
+    dot[1][dt] = frag_tr(do_lds, st.fa, 32 * qt + 16, dt);
+    qt_[1][dt] = frag_tr(q_lds, st.fa, 32 * qt + 16, dt);
+  }
+  __builtin_amdgcn_sched_barrier(0);
   if (MASK) {
     // element r = 4a + b is (query qs32 + 8a + 4 lh + b, key kj); queries past the block end are
     // clamped duplicates of its last row and must not count
@@ -259,14 +295,9 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
       }
     }
   }
-  // rows of the C tile are queries 8a + 4 lh + b: their LSE / delta come from LDS (broadcast reads)
-  const float* lse_lds = (const float*)(stage + kStageLse) + 32 * qt + 4 * lh;
-  const float* dl_lds = (const float*)(stage + kStageDelta) + 32 * qt + 4 * lh;
 #pragma unroll
   for (int a = 0; a < 4; a++) {
-    const float4 l4 = *(const float4*)(lse_lds + 8 * a);
-    const float4 d4 = *(const float4*)(dl_lds + 8 * a);
-    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+    const float lv[4] = {l4[a].x, l4[a].y, l4[a].z, l4[a].w}, dv4[4] = {d4[a].x, d4[a].y, d4[a].z, d4[a].w};
 #pragma unroll
     for (int b = 0; b < 4; b++) {
       const int r = 4 * a + b;
@@ -280,8 +311,8 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
     const bf16x8 pb = pack_frag(s, c), dsb = pack_frag(dp, c);
 #pragma unroll
     for (int dt = 0; dt < 4; dt++) {
-      st.dv[dt] = mfma(frag_tr(do_lds, st.fa, 32 * qt + 16 * c, dt), pb, st.dv[dt]);
-      st.dk[dt] = mfma(frag_tr(q_lds, st.fa, 32 * qt + 16 * c, dt), dsb, st.dk[dt]);
+      st.dv[dt] = mfma(dot[c][dt], pb, st.dv[dt]);
+      st.dk[dt] = mfma(qt_[c][dt], dsb, st.dk[dt]);
     }
   }
 }
@@ -329,8 +360,6 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   }
   const float c_log2 = t.scale * kLog2e;
 
-  typedef __attribute__((address_space(3))) void* lds_p;
-  typedef __attribute__((address_space(1))) const void* glb_p;
   QIter it(g, w.unit, G);
   auto issue = [&](char* stage) {
     const int head = hk * G + it.hh;
@@ -338,12 +367,9 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
     st.dmaq.load(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, it.qs, last, wave);
     st.dmao.load(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, it.qs, last, wave);
     const int qrow = min(it.qs + lane, last);
-    if (wave == 0)
-      __builtin_amdgcn_global_load_lds((glb_p)(t.lse2 + (int64_t)head * t.total_tokens + qrow), (lds_p)(stage + kStageLse), 4, 0, 0);
-    if (wave == 1)
-      __builtin_amdgcn_global_load_lds((glb_p)(t.delta + (int64_t)head * t.total_tokens + qrow), (lds_p)(stage + kStageDelta), 4, 0, 0);
-    if (wave == 2 && it.kind == 2)
-      __builtin_amdgcn_global_load_lds((glb_p)(t.ranges + (int64_t)qrow * 4), (lds_p)(stage + kStageRanges), 16, 0, 0);
+    if (wave == 0) dma4((unsigned)qrow * 4u, uni_ptr(t.lse2 + (int64_t)head * t.total_tokens), lds_addr(stage + kStageLse));
+    if (wave == 1) dma4((unsigned)qrow * 4u, uni_ptr(t.delta + (int64_t)head * t.total_tokens), lds_addr(stage + kStageDelta));
+    if (wave == 2 && it.kind == 2) dma16((unsigned)qrow * 16u, uni_ptr(t.ranges), lds_addr(stage + kStageRanges));
   };
   bool have = it.next(k_lo);
   if (have) issue(stage0);

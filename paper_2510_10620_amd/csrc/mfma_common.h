@@ -125,6 +125,15 @@ __device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int c) {
 __device__ __forceinline__ void dma16(unsigned voffset, const void* sbase, unsigned lds) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voffset), "s"(sbase), "s"(lds) : "memory");
 }
+__device__ __forceinline__ void dma4(unsigned voffset, const void* sbase, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voffset), "s"(sbase), "s"(lds) : "memory");
+}
+// a pointer that is wave-uniform by construction, made provably so (it must live in SGPRs)
+__device__ __forceinline__ const void* uni_ptr(const void* p) {
+  const uint64_t v = (uint64_t)p;
+  return (const void*)(((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
+                       (unsigned)__builtin_amdgcn_readfirstlane((int)v));
+}
 // s_waitcnt vmcnt(N) only (expcnt and lgkmcnt left at their maxima)
 #define DCP_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N)&15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
