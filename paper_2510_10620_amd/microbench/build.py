@@ -3,7 +3,8 @@
     python -m paper_2510_10620_amd.microbench.build      # -> paper_2510_10620_amd/microbench/bin/<name>
 
   isa_probe          semantics of ds_read_b64_tr_b16 and the 32x32x16 / 16x16x32 bf16 MFMA operand layouts
-  clock_mfma_peak    shader clock and the peak rate of v_mfma_f32_32x32x16_bf16
+  clock_mfma_peak    shader clock and the rate of v_mfma_f32_32x32x16_bf16, on constants and on data-like operands
+  mfma_chains        cycles per MFMA when 1..8 accumulators are updated round-robin (dependent-issue cost)
   lds_bandwidth      ds_read_b128 / ds_read_b64 / ds_read_b64_tr_b16 bytes per clock per CU
   lds_patterns       ds_read_b128 rate of the kernels' swizzled tile layout against other layouts
   loop_ingredients   MFMA rate of the attention inner-loop skeleton as LDS operands, softmax ALU work
