@@ -184,6 +184,7 @@ def main():
                  table_rows=int(len(table)), n_seq=int(len(w.cu_seqlens) - 1))
     if not args.no_extra:
         extra["share"] = share_section(torch, P, W, np, steps=max(3, args.steps // 4), warmup=2)
+        extra["blockwise_copy"] = copy_section(torch, P, np, plan, q, steps=max(3, args.steps // 2))
 
     # one plain copy of known size (256 MiB read + 256 MiB written) through the library's sum
     # kernel with a single part: the reference dispatch that scales hardware byte counters
@@ -264,6 +265,31 @@ def share_section(torch, P, W, np, steps, warmup):
     res["merge_GBps"] = round(merge_bytes / (res["merge_ms"] * 1e-3) / 1e9, 1)
     res["merge_frac_hbm"] = round(res["merge_GBps"] / PEAK_HBM_GBPS, 3)
     return res
+
+
+def copy_section(torch, P, np, plan, q, steps):
+    """Blockwise Copy of every Q block of the workload from the packed tensor into a block buffer with
+    permuted slots (the executor's buffer fill): algorithmic bytes = read + write of every row."""
+    blk_start = plan.export("BLK_START").astype(np.int64)
+    blk_len = plan.export("BLK_LEN").astype(np.int64)
+    B = int(blk_len.max())
+    slots = np.random.default_rng(11).permutation(len(blk_start))
+    entries = np.stack([blk_start, slots * B, blk_len], axis=1).astype(np.int32)
+    buf = torch.empty((len(blk_start) * B,) + tuple(q.shape[1:]), dtype=q.dtype, device="cuda")
+    cl = P.CopyList(entries, q.shape[0], buf.shape[0])
+    P.dcp_blockwise_copy(cl, q, buf)
+    torch.cuda.synchronize()
+    P.dcp_profile_enable(True)
+    for _ in range(steps):
+        P.dcp_blockwise_copy(cl, q, buf)
+    torch.cuda.synchronize()
+    tot, n = P.dcp_profile_read("copy")
+    P.dcp_profile_enable(False)
+    ms = tot / max(n, 1)
+    nbytes = 2 * int(blk_len.sum()) * q[0].numel() * q.element_size()
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    return dict(workload=f"{len(entries)} Q blocks ({int(blk_len.sum())} rows of {q[0].numel() * q.element_size()} B) packed -> permuted slots",
+                ms=round(ms, 4), GBps=round(gbps, 1), frac_hbm=round(gbps / PEAK_HBM_GBPS, 3))
 
 
 if __name__ == "__main__":

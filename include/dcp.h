@@ -184,12 +184,33 @@ dcp_status_t dcp_sum_partials(const void* const* parts_host_array_of_device_ptrs
                               int32_t parts_dtype, void* dst, int32_t dst_dtype, int64_t n_elems,
                               void* stream);
 
+/* Blockwise Copy (Sec. 5 "Blockwise Copy": several data blocks copied inside one device's memory
+ * by one fused kernel; used to manage the block buffers of Sec. 5 "Block buffers").
+ * A copy list is built once per iteration, like the plan (Sec. 3.2), and replayed for every layer.
+ *   entries_host  host int32 [n,3] rows (src_row, dst_row, n_rows), copied; a row is one row of a
+ *                 2-D view of a buffer (e.g. one token's [heads, D] slab)
+ *   src_rows, dst_rows   number of rows the source / destination buffer holds
+ * DCP_ERR_BAD_TABLE: a negative field, a range that leaves its buffer, or two destination ranges
+ * that overlap.  n = 0 is legal (the copy does nothing).  The list owns a small device array,
+ * created on the device that is current at the first dcp_blockwise_copy and freed by destroy. */
+typedef struct dcp_copy_list dcp_copy_list_t;
+dcp_status_t dcp_copy_list_create(dcp_copy_list_t** list, const int32_t* entries_host, int64_t n,
+                                  int64_t src_rows, int64_t dst_rows);
+dcp_status_t dcp_copy_list_destroy(dcp_copy_list_t* list);
+/* dst[(dst_row + r) * dst_row_stride + 0 .. row_bytes) = src[(src_row + r) * src_row_stride + ..]
+ * for every entry and r < n_rows.  src, dst: device, 16-byte aligned; strides and row_bytes in
+ * bytes, multiples of 16, stride >= row_bytes.  The two buffers may be the same allocation
+ * (same pointer and stride) only if no destination range of the list overlaps a source range;
+ * any other overlap of the two buffers is rejected (DCP_ERR_INVALID_ARG).  Asynchronous on stream. */
+dcp_status_t dcp_blockwise_copy(dcp_copy_list_t* list, const void* src, int64_t src_row_stride,
+                                void* dst, int64_t dst_row_stride, int64_t row_bytes, void* stream);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
  * bracketed by hipEvents recorded on the launch stream (the kernels of one backward call are timed
  * one by one).  dcp_profile_read synchronises on the recorded events, returns the summed duration
  * and the number of launches of one kernel since the last enable, and leaves the records in place;
  * dcp_profile_enable(1) clears them.  Not thread-safe; meant for a single benchmarking thread. */
-typedef enum { DCP_K_FWD = 0, DCP_K_MERGE = 1, DCP_K_DELTA = 2, DCP_K_DQ = 3, DCP_K_DKV = 4, DCP_K_SUM = 5 } dcp_kernel_id_t;
+typedef enum { DCP_K_FWD = 0, DCP_K_MERGE = 1, DCP_K_DELTA = 2, DCP_K_DQ = 3, DCP_K_DKV = 4, DCP_K_SUM = 5, DCP_K_COPY = 6 } dcp_kernel_id_t;
 dcp_status_t dcp_profile_enable(int32_t enable);
 dcp_status_t dcp_profile_read(int32_t kernel_id, double* total_ms, int64_t* launches);
 

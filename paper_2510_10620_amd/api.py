@@ -195,7 +195,44 @@ def dcp_sum_partials(parts, dst):
                                         dst.numel(), _stream()))
 
 
-KERNEL_IDS = dict(fwd=0, merge=1, delta=2, dq=3, dkv=4, sum=5)
+class CopyList:
+    """Blockwise Copy list: entries int32 [n,3] (src_row, dst_row, n_rows) over 2-D row views of two buffers."""
+
+    def __init__(self, entries, src_rows, dst_rows):
+        e = np.ascontiguousarray(np.asarray(entries, dtype=np.int32).reshape(-1, 3))
+        self.n = e.shape[0]
+        self.src_rows, self.dst_rows = int(src_rows), int(dst_rows)
+        h = ctypes.c_void_p()
+        _check(_lib.load().dcp_copy_list_create(ctypes.byref(h), e.ctypes.data_as(_lib.i32p), self.n, self.src_rows, self.dst_rows))
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            _lib.load().dcp_copy_list_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def dcp_blockwise_copy(copy_list, src, dst):
+    """src, dst: tensors whose first axis is the row and whose rows are contiguous (e.g. [rows, H, D])."""
+    def row_view(t):
+        assert t.dim() >= 1 and (t.dim() == 1 or t[0].is_contiguous()), "rows must be contiguous"
+        row_bytes = (t[0].numel() if t.dim() > 1 else 1) * t.element_size()
+        stride = (t.stride(0) if t.shape[0] > 1 else (t[0].numel() if t.dim() > 1 else 1)) * t.element_size()
+        return row_bytes, stride
+    rb_s, st_s = row_view(src)
+    rb_d, st_d = row_view(dst)
+    assert rb_s == rb_d, "source and destination rows differ in size"
+    assert src.shape[0] == copy_list.src_rows and dst.shape[0] == copy_list.dst_rows
+    _check(_lib.load().dcp_blockwise_copy(copy_list.handle, src.data_ptr(), st_s, dst.data_ptr(), st_d, rb_s, _stream()))
+
+
+KERNEL_IDS = dict(fwd=0, merge=1, delta=2, dq=3, dkv=4, sum=5, copy=6)
 
 
 def dcp_profile_enable(enable):

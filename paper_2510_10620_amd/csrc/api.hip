@@ -1,6 +1,9 @@
 // Launching entry points of the C ABI: argument validation (host side, complete before any
 // launch), kernel-family selection, and the enqueue of the kernels on the caller's stream.
+#include <algorithm>
 #include <cmath>
+#include <memory>
+#include <string>
 #include <vector>
 
 #include "kernels.h"
@@ -10,7 +13,7 @@ using namespace dcp;
 namespace dcp {
 struct ProfRec { hipEvent_t a, b; };
 static bool g_prof_on = false;
-static std::vector<ProfRec> g_prof[6];
+static std::vector<ProfRec> g_prof[7];
 ProfScope::ProfScope(int id_, hipStream_t s_) : id(id_), s(s_) {
   if (!g_prof_on) return;
   hipEvent_t a = nullptr;
@@ -35,7 +38,7 @@ extern "C" dcp_status_t dcp_profile_enable(int32_t enable) {
 }
 
 extern "C" dcp_status_t dcp_profile_read(int32_t kernel_id, double* total_ms, int64_t* launches) {
-  if (kernel_id < 0 || kernel_id > 5 || !total_ms || !launches) return fail(DCP_ERR_INVALID_ARG, "bad kernel id or NULL output");
+  if (kernel_id < 0 || kernel_id > 6 || !total_ms || !launches) return fail(DCP_ERR_INVALID_ARG, "bad kernel id or NULL output");
   double tot = 0;
   for (auto& r : g_prof[kernel_id]) {
     DCP_HIP_TRY(hipEventSynchronize(r.b));
@@ -220,6 +223,91 @@ extern "C" dcp_status_t dcp_sum_partials(const void* const* parts, int32_t n_par
     if (!parts[i] || !aligned16(parts[i])) return fail(DCP_ERR_INVALID_ARG, "a partial pointer is NULL or misaligned");
   ProfScope ps(DCP_K_SUM, (hipStream_t)stream);
   return stream_sum(parts, n_parts, parts_dtype, dst, dst_dtype, n_elems, (hipStream_t)stream);
+}
+
+extern "C" dcp_status_t dcp_copy_list_create(dcp_copy_list_t** list, const int32_t* entries, int64_t n, int64_t src_rows,
+                                             int64_t dst_rows) {
+  if (!list) return fail(DCP_ERR_INVALID_ARG, "list is NULL");
+  *list = nullptr;
+  if (n < 0 || (n > 0 && !entries)) return fail(DCP_ERR_INVALID_ARG, "entries is NULL or n < 0");
+  if (src_rows < 0 || dst_rows < 0 || src_rows > INT32_MAX || dst_rows > INT32_MAX)
+    return fail(DCP_ERR_INVALID_ARG, "src_rows / dst_rows must lie in [0, 2^31)");
+  std::unique_ptr<dcp_copy_list> cl(new dcp_copy_list);
+  cl->src_rows = src_rows; cl->dst_rows = dst_rows;
+  std::vector<std::pair<int64_t, int64_t>> dsts, srcs;   // [begin, end)
+  for (int64_t i = 0; i < n; i++) {
+    const int64_t sr = entries[3 * i], dr = entries[3 * i + 1], nr = entries[3 * i + 2];
+    if (sr < 0 || dr < 0 || nr < 0) return fail(DCP_ERR_BAD_TABLE, "copy entry " + std::to_string(i) + " has a negative field");
+    if (sr + nr > src_rows) return fail(DCP_ERR_BAD_TABLE, "copy entry " + std::to_string(i) + " reads past the source buffer");
+    if (dr + nr > dst_rows) return fail(DCP_ERR_BAD_TABLE, "copy entry " + std::to_string(i) + " writes past the destination buffer");
+    if (nr == 0) continue;
+    dsts.push_back({dr, dr + nr});
+    srcs.push_back({sr, sr + nr});
+    for (int64_t r = 0; r < nr; r += kCopyChunkRows) {
+      cl->chunks.push_back((int32_t)(sr + r));
+      cl->chunks.push_back((int32_t)(dr + r));
+      cl->chunks.push_back((int32_t)std::min<int64_t>(kCopyChunkRows, nr - r));
+    }
+  }
+  std::sort(dsts.begin(), dsts.end());
+  for (size_t i = 1; i < dsts.size(); i++)
+    if (dsts[i].first < dsts[i - 1].second) return fail(DCP_ERR_BAD_TABLE, "two copy entries write overlapping destination rows");
+  // would a destination range overlap a source range if both buffers were the same allocation?
+  std::sort(srcs.begin(), srcs.end());
+  size_t j = 0;
+  for (size_t i = 0; i < dsts.size() && cl->alias_safe; i++) {
+    while (j < srcs.size() && srcs[j].second <= dsts[i].first) j++;
+    for (size_t k = j; k < srcs.size() && srcs[k].first < dsts[i].second; k++)
+      if (srcs[k].second > dsts[i].first) { cl->alias_safe = false; break; }
+  }
+  *list = cl.release();
+  return DCP_OK;
+}
+
+extern "C" dcp_status_t dcp_copy_list_destroy(dcp_copy_list_t* list) {
+  if (!list) return DCP_OK;
+  if (list->d_chunks) (void)hipFree(list->d_chunks);
+  delete list;
+  return DCP_OK;
+}
+
+extern "C" dcp_status_t dcp_blockwise_copy(dcp_copy_list_t* list, const void* src, int64_t src_stride, void* dst,
+                                           int64_t dst_stride, int64_t row_bytes, void* stream) {
+  if (!list) return fail(DCP_ERR_INVALID_ARG, "list is NULL");
+  if (row_bytes <= 0 || row_bytes % 16 || row_bytes / 16 > (1 << 24)) return fail(DCP_ERR_INVALID_ARG, "row_bytes must be a positive multiple of 16 (at most 2^28)");
+  if (src_stride < row_bytes || dst_stride < row_bytes || src_stride % 16 || dst_stride % 16)
+    return fail(DCP_ERR_INVALID_ARG, "row strides must be multiples of 16 and at least row_bytes");
+  if (list->chunks.empty()) return DCP_OK;
+  if (!src || !dst || !aligned16(src) || !aligned16(dst)) return fail(DCP_ERR_INVALID_ARG, "src or dst is NULL or misaligned");
+  {
+    // extents the list can touch
+    const char* s0 = (const char*)src; const char* s1 = s0 + (list->src_rows - 1) * src_stride + row_bytes;
+    const char* d0 = (const char*)dst; const char* d1 = d0 + (list->dst_rows - 1) * dst_stride + row_bytes;
+    const bool overlap = list->src_rows > 0 && list->dst_rows > 0 && s0 < d1 && d0 < s1;
+    if (overlap && !(src == dst && src_stride == dst_stride && list->alias_safe))
+      return fail(DCP_ERR_INVALID_ARG, "source and destination buffers overlap (allowed only as the same buffer with a list whose destination ranges avoid its source ranges)");
+  }
+  hipStream_t s = (hipStream_t)stream;
+  {
+    std::lock_guard<std::mutex> lock(list->mu);
+    int dev = -1;
+    DCP_HIP_TRY(hipGetDevice(&dev));
+    if (list->d_chunks && list->device != dev) return fail(DCP_ERR_INVALID_ARG, "copy list was first used on another device");
+    if (!list->d_chunks) {
+      const size_t bytes = list->chunks.size() * sizeof(int32_t);
+      DCP_HIP_TRY(hipMalloc((void**)&list->d_chunks, bytes));
+      hipError_t e = hipMemcpyAsync(list->d_chunks, list->chunks.data(), bytes, hipMemcpyHostToDevice, s);
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      if (e != hipSuccess) {
+        (void)hipFree(list->d_chunks);
+        list->d_chunks = nullptr;
+        return fail(DCP_ERR_HIP, std::string("copy list upload: ") + hipGetErrorString(e));
+      }
+      list->device = dev;
+    }
+  }
+  ProfScope ps(DCP_K_COPY, s);
+  return stream_copy(list->d_chunks, (int64_t)(list->chunks.size() / 3), src, src_stride, dst, dst_stride, row_bytes, s);
 }
 
 extern "C" const char* dcp_version(void) { return "dcp_attn 0.1 (gfx950)"; }

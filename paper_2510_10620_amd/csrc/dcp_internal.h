@@ -78,3 +78,15 @@ struct dcp_plan {
   // group id: 0 fwd, 1 bwdq, 2 bwdkv
   dcp_status_t group_for(int group_id, int tile_rows, hipStream_t stream, dcp::DevGroup* out);
 };
+
+// Blockwise Copy list: validated entries cut into chunks of at most kCopyChunkRows rows.
+static constexpr int kCopyChunkRows = 8;
+struct dcp_copy_list {
+  int64_t src_rows = 0, dst_rows = 0;
+  bool alias_safe = true;            // no destination range overlaps a source range (as row intervals)
+  std::vector<int32_t> chunks;       // [n_chunks, 3]
+  std::mutex mu;
+  int device = -1;
+  int32_t* d_chunks = nullptr;
+};
+

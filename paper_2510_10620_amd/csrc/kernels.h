@@ -56,4 +56,8 @@ dcp_status_t stream_delta(const void* o, int64_t o_st, int64_t o_sh, const void*
 dcp_status_t stream_sum(const void* const* parts, int32_t n_parts, int32_t parts_dtype, void* dst, int32_t dst_dtype,
                         int64_t n, hipStream_t s);
 
+// chunks: device int32 [n_chunks, 3] (src_row, dst_row, n_rows)
+dcp_status_t stream_copy(const int32_t* chunks, int64_t n_chunks, const void* src, int64_t src_stride, void* dst,
+                         int64_t dst_stride, int64_t row_bytes, hipStream_t s);
+
 }  // namespace dcp

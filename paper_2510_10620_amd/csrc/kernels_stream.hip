@@ -189,4 +189,42 @@ dcp_status_t stream_sum(const void* const* parts, int32_t n_parts, int32_t parts
   return DCP_OK;
 }
 
+// ------------------------------------------------------------------------------------ copy
+// Blockwise Copy: one workgroup per chunk of at most kCopyChunkRows rows, 16 bytes per lane and
+// load, four loads in flight per lane.  HBM-bound: 2 * row_bytes algorithmic bytes per row.
+__global__ __launch_bounds__(256) void copy_kernel(const int32_t* __restrict__ chunks, int64_t n_chunks,
+                                                   const char* __restrict__ src, int64_t src_stride,
+                                                   char* __restrict__ dst, int64_t dst_stride, int32_t vec_per_row) {
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const int32_t sr = chunks[3 * c], dr = chunks[3 * c + 1], nr = chunks[3 * c + 2];
+    const char* sp = src + (int64_t)sr * src_stride;
+    char* dp = dst + (int64_t)dr * dst_stride;
+    const int32_t total = nr * vec_per_row;
+    if (src_stride == (int64_t)vec_per_row * 16 && dst_stride == src_stride) {
+      // rows are back to back in both buffers: one linear span
+      int32_t i = threadIdx.x;
+      for (; i + 768 < total; i += 1024) {
+        const uint4 a = ((const uint4*)sp)[i], b = ((const uint4*)sp)[i + 256], e = ((const uint4*)sp)[i + 512], f = ((const uint4*)sp)[i + 768];
+        ((uint4*)dp)[i] = a; ((uint4*)dp)[i + 256] = b; ((uint4*)dp)[i + 512] = e; ((uint4*)dp)[i + 768] = f;
+      }
+      for (; i < total; i += 256) ((uint4*)dp)[i] = ((const uint4*)sp)[i];
+    } else {
+      for (int32_t i = threadIdx.x; i < total; i += 256) {
+        const int32_t r = i / vec_per_row, v = i - r * vec_per_row;
+        *(uint4*)(dp + (int64_t)r * dst_stride + 16 * v) = *(const uint4*)(sp + (int64_t)r * src_stride + 16 * v);
+      }
+    }
+  }
+}
+
+dcp_status_t stream_copy(const int32_t* chunks, int64_t n_chunks, const void* src, int64_t src_stride, void* dst,
+                         int64_t dst_stride, int64_t row_bytes, hipStream_t s) {
+  if (n_chunks == 0) return DCP_OK;
+  dim3 grid((unsigned)std::min<int64_t>(n_chunks, 256 * 64)), block(256);
+  hipLaunchKernelGGL(copy_kernel, grid, block, 0, s, chunks, n_chunks, (const char*)src, src_stride, (char*)dst, dst_stride,
+                     (int32_t)(row_bytes / 16));
+  DCP_HIP_TRY(hipGetLastError());
+  return DCP_OK;
+}
+
 }  // namespace dcp

@@ -181,3 +181,49 @@ def test_delta_and_sum_partials_streaming_kernels():
     P.dcp_sum_partials(parts, dst32)
     err = H.max_abs(H.from_torch(dst32), ref)
     assert err <= 1e-5, err
+
+
+def test_blockwise_copy_bit_exact():
+    """Blockwise Copy between a packed tensor and a block buffer (and inside one buffer), bit for bit against
+    the oracle's row loops: ragged last blocks, rows narrower than a lane group, padded row strides, and a
+    second, smaller list on the same buffers."""
+    import torch
+    import paper_2510_10620_amd as P
+    from oracle import blockbuf as BB
+    rng = np.random.default_rng(41)
+    B = 48
+    cu = np.concatenate([[0], np.cumsum([200, 37, 48, 301])]).astype(np.int32)
+    part = OB.block_partition(cu, B)
+    bs, bl = part["blk_start"], part["blk_end"] - part["blk_start"]
+    n_slots = len(bs) + 2
+    slots = rng.permutation(n_slots)[:len(bs)].astype(np.int32)
+    T = int(cu[-1])
+    for shape, dtype in (((4, 128), np.uint16), ((1, 8), np.uint16), ((2, 36), np.float32)):
+        x = rng.integers(0, 60000, size=(T,) + shape).astype(dtype)
+        to_buf = BB.copy_entries_for_blocks(bs, bl, slots, B, to_buffer=True)
+        ref_buf = BB.blockwise_copy(x, np.full((n_slots * B,) + shape, 7, dtype=dtype), to_buf)
+        tx = torch.from_numpy(x.view(np.int16) if dtype == np.uint16 else x).cuda()
+        tbuf = torch.full((n_slots * B,) + shape, 7, dtype=tx.dtype, device="cuda")
+        cl = P.CopyList(to_buf, T, n_slots * B)
+        P.dcp_blockwise_copy(cl, tx, tbuf)
+        got = tbuf.cpu().numpy()
+        assert np.array_equal(got.view(dtype), ref_buf), (shape, "packed -> buffer")
+        # back through a padded destination (row stride > row bytes)
+        back = BB.copy_entries_for_blocks(bs, bl, slots, B, to_buffer=False)
+        wide = torch.zeros((T, shape[0] * 2, shape[1]), dtype=tx.dtype, device="cuda")
+        P.dcp_blockwise_copy(P.CopyList(back, n_slots * B, T), tbuf, wide[:, :shape[0]])
+        assert np.array_equal(wide[:, :shape[0]].cpu().numpy().view(dtype), x), (shape, "buffer -> packed, strided")
+        assert int(wide[:, shape[0]:].abs().sum()) == 0, "padding was written"
+        # a smaller list on the same buffers: one block moved inside the buffer to a free slot
+        free = sorted(set(range(n_slots)) - set(slots.tolist()))[0]
+        b = 2
+        inside = np.array([[slots[b] * B, free * B, bl[b]]], dtype=np.int32)
+        ref2 = BB.blockwise_copy(ref_buf.copy(), ref_buf.copy(), inside)
+        P.dcp_blockwise_copy(P.CopyList(inside, n_slots * B, n_slots * B), tbuf, tbuf)
+        assert np.array_equal(tbuf.cpu().numpy().view(dtype), ref2), (shape, "inside one buffer")
+    # same buffer with a destination that overlaps a source range is refused
+    bad = P.CopyList(np.array([[0, 10, 20]], dtype=np.int32), n_slots * B, n_slots * B)
+    with pytest.raises(P.DcpError):
+        P.dcp_blockwise_copy(bad, tbuf, tbuf)
+    # an empty list does nothing
+    P.dcp_blockwise_copy(P.CopyList(np.zeros((0, 3), np.int32), T, n_slots * B), tx, tbuf)

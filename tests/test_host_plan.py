@@ -158,3 +158,21 @@ def test_share_dealing_is_a_partition_with_valid_slots():
     assert np.array_equal(plan.export("SLOT_QBLK"), slot_q)
     mptr = plan.export("MERGE_PTR")
     assert (np.diff(mptr) <= n_div).all() and mptr[-1] == n_slots
+
+
+# ------------------------------------------------------------------ Blockwise Copy list (host side)
+def _copy_err(entries, src_rows, dst_rows):
+    with pytest.raises(P.DcpError) as e:
+        P.CopyList(entries, src_rows, dst_rows)
+    return e.value
+
+
+def test_copy_list_validation():
+    P.CopyList(np.zeros((0, 3), np.int32), 0, 0).close()
+    P.CopyList([[0, 5, 5], [5, 0, 5], [3, 10, 0]], 10, 10).close()
+    assert _copy_err([[0, 0, -1]], 4, 4).status == P.DCP_ERR_BAD_TABLE
+    assert _copy_err([[-1, 0, 1]], 4, 4).status == P.DCP_ERR_BAD_TABLE
+    assert _copy_err([[2, 0, 3]], 4, 4).status == P.DCP_ERR_BAD_TABLE          # reads past the source
+    assert _copy_err([[0, 2, 3]], 4, 4).status == P.DCP_ERR_BAD_TABLE          # writes past the destination
+    assert _copy_err([[0, 0, 3], [4, 2, 2]], 8, 8).status == P.DCP_ERR_BAD_TABLE  # destinations overlap
+    assert _copy_err([[0, 0, 1]], -1, 4).status == P.DCP_ERR_INVALID_ARG

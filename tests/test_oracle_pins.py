@@ -421,3 +421,58 @@ def test_row_window_matches_full_computation():
     # keys >= 60 are seen only by queries >= 60 (every mask here is causal-bounded)
     np.testing.assert_allclose(dkw[60:90], dk[60:90], atol=1e-12)
     np.testing.assert_allclose(dvw[60:90], dv[60:90], atol=1e-12)
+
+
+# ------------------------------------------------------------------ block buffers, Blockwise Copy
+def _blocks_and_slots(rng, lens, B):
+    from oracle import blocks as OB_
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    part = OB_.block_partition(cu, B)
+    bs, bl = part["blk_start"], part["blk_end"] - part["blk_start"]
+    n_slots = len(bs) + 3
+    slots = rng.permutation(n_slots)[:len(bs)].astype(np.int32)
+    return cu, np.asarray(bs), np.asarray(bl), slots, n_slots
+
+
+def test_blockwise_copy_is_row_assignment():
+    """Sec. 5 "Blockwise Copy": against numpy's own fancy-index row assignment, and an identity round trip."""
+    from oracle import blockbuf as BB
+    rng = np.random.default_rng(7)
+    src = rng.standard_normal((40, 3, 4))
+    entries = np.array([[0, 10, 5], [30, 0, 10], [12, 25, 1], [7, 30, 0]], dtype=np.int32)
+    dst = np.full((35, 3, 4), -1.0)
+    BB.blockwise_copy(src, dst, entries)
+    want = np.full((35, 3, 4), -1.0)
+    idx_s = np.concatenate([np.arange(s, s + n) for s, _, n in entries])
+    idx_d = np.concatenate([np.arange(d, d + n) for _, d, n in entries])
+    want[idx_d] = src[idx_s]
+    assert np.array_equal(dst, want)
+    assert (dst[15:25] == -1).all() and (dst[26:30] == -1).all()      # rows no entry names stay untouched
+
+
+def test_block_buffer_gather_scatter_and_copy_lists_agree():
+    """Sec. 5 "Block buffers": packed -> buffer -> packed is the identity on the rows blocks use; the copy
+    list route (copy_entries_for_blocks + blockwise_copy) equals the direct gather (two code paths)."""
+    from oracle import blockbuf as BB
+    rng = np.random.default_rng(8)
+    B = 6
+    cu, bs, bl, slots, n_slots = _blocks_and_slots(rng, [13, 6, 20, 1], B)
+    T = int(cu[-1])
+    x = rng.standard_normal((T, 2, 3))
+    buf = BB.gather_blocks(x, bs, bl, slots, n_slots, B, fill=np.nan)
+    assert np.array_equal(BB.scatter_blocks(buf, bs, bl, slots, B, T), x)
+    # every buffer row is either a block row or still the fill value, and the counts match
+    assert np.isnan(buf).all(axis=(1, 2)).sum() == n_slots * B - T
+    to_buf = BB.copy_entries_for_blocks(bs, bl, slots, B, to_buffer=True)
+    buf2 = BB.blockwise_copy(x, np.full_like(buf, np.nan), to_buf)
+    assert np.array_equal(np.nan_to_num(buf2, nan=-7.0), np.nan_to_num(buf, nan=-7.0))
+    back = BB.copy_entries_for_blocks(bs, bl, slots, B, to_buffer=False)
+    assert np.array_equal(BB.blockwise_copy(buf2, np.zeros_like(x), back), x)
+    # block b, row r sits at slot * B + r
+    b = 3
+    assert np.array_equal(buf[slots[b] * B + 2], x[bs[b] + 2])
+    # [H, T] scalars take the same route
+    l = rng.standard_normal((2, T))
+    lb = BB.gather_rows_hT(l, bs, bl, slots, n_slots, B, fill=np.inf)
+    assert np.array_equal(BB.scatter_rows_hT(lb, bs, bl, slots, B, T), l)
+    assert lb[1, slots[b] * B + 2] == l[1, bs[b] + 2]
