@@ -82,6 +82,22 @@ dcp_status_t dcp_count_pairs(const int32_t* cu_seqlens_host, int32_t n_seq, int3
                              const int32_t* table_host, int64_t n_entries,
                              const int32_t* attn_ranges_host, int64_t* pairs_out);
 
+/* Block buffers (Sec. 5 "Block buffers", and "Blockwise Attention": input and output blocks are
+ * given by the buffer's start address and per-block offsets recorded with the block table, as in
+ * paged attention).  After this call the tensors of every launch with this plan are block buffers:
+ *   q, out, dout, dq : [n_q_slots * block_size, Hq, D];  lse (and the backward workspace) : [Hq, n_q_slots * block_size]
+ *   k, v, dk, dv     : [n_kv_slots * block_size, Hkv, D]
+ * and row r of block b lives at row slot[b] * block_size + r of its buffer.  attn_ranges stays
+ * indexed by packed token (it is mask metadata, not a data block), and so do the ranges it holds.
+ *   q_slot, kv_slot  host int32 [n_blocks], copied; -1 = the block is not in that buffer
+ * Blocks with q_slot -1 get no output (their rows do not exist); rows of the buffers that no block
+ * owns are never read or written by the attention kernels.  dcp_bwd_delta works on whole buffers.
+ * Must be called before the plan is first used on a device (DCP_ERR_INVALID_ARG otherwise).
+ * DCP_ERR_BAD_TABLE: a slot out of range, two blocks in one slot, or a block the table uses
+ * (as q_blk / kv_blk of a non-SKIP row) that is absent from the buffer it is needed in. */
+dcp_status_t dcp_plan_set_block_buffers(dcp_plan_t* plan, const int32_t* q_slot_host, int32_t n_q_slots,
+                                        const int32_t* kv_slot_host, int32_t n_kv_slots);
+
 /* ---------------------------------------------------------------------------------------------
  * Plan: the executor's per-iteration state (Sec. 3.2: the plan is set once per iteration and
  * shared by all layers).  Validates the table, derives block token ranges, groups rows by output

@@ -96,6 +96,14 @@ def dcp_plan_create(cu_seqlens, block_size, table, out_slot=None, n_slots=0):
     return Plan(h, n_slots if out_slot is not None else 0, block_size, int(cu[-1]) if len(cu) else 0)
 
 
+def dcp_plan_set_block_buffers(plan, q_slot, n_q_slots, kv_slot, n_kv_slots):
+    """Q-type tensors become [n_q_slots * block_size, ...] buffers, KV-type [n_kv_slots * block_size, ...]."""
+    qs, qs_p = _i32(q_slot)
+    ks, ks_p = _i32(kv_slot)
+    _check(_lib.load().dcp_plan_set_block_buffers(plan.handle, qs_p, n_q_slots, ks_p, n_kv_slots))
+    plan.q_rows, plan.kv_rows = n_q_slots * plan.block_size, n_kv_slots * plan.block_size
+
+
 def dcp_plan_destroy(plan):
     _check(_lib.load().dcp_plan_destroy(plan.handle))
     plan.handle = None

@@ -96,7 +96,7 @@ static KTensors pack(const dcp_plan_t* plan, const dcp_tensors_t* t) {
   k.v_st = t->v_stride_t; k.v_sh = t->v_stride_h; k.o_st = t->o_stride_t; k.o_sh = t->o_stride_h;
   k.do_st = t->do_stride_t; k.do_sh = t->do_stride_h; k.dq_st = t->dq_stride_t; k.dq_sh = t->dq_stride_h;
   k.dk_st = t->dk_stride_t; k.dk_sh = t->dk_stride_h; k.dv_st = t->dv_stride_t; k.dv_sh = t->dv_stride_h;
-  k.total_tokens = plan->total_tokens;
+  k.q_rows = plan->q_rows;
   k.hq = t->hq; k.hkv = t->hkv; k.d = t->d; k.block_size = plan->block_size;
   k.scale = t->softmax_scale;
   k.use_slots = plan->use_slots ? 1 : 0;
@@ -140,8 +140,8 @@ extern "C" dcp_status_t dcp_merge_partials(dcp_plan_t* plan, const void* o_part,
   hipStream_t s = (hipStream_t)stream;
   if ((st = plan->ensure_device(s)) != DCP_OK) return st;
   ProfScope ps(DCP_K_MERGE, s);
-  return stream_merge(plan->d_merge_ptr, plan->d_merge_idx, plan->d_fwd.blk_start, plan->d_fwd.blk_len, plan->n_blocks,
-                      plan->block_size, o_part, lse_part, out, o_stride_t, o_stride_h, lse, plan->total_tokens, hq, d,
+  return stream_merge(plan->d_merge_ptr, plan->d_merge_idx, plan->d_q_mem0, plan->d_fwd.blk_len, plan->n_blocks,
+                      plan->block_size, o_part, lse_part, out, o_stride_t, o_stride_h, lse, plan->q_rows, hq, d,
                       dtype, s);
 }
 
@@ -163,7 +163,7 @@ extern "C" dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_toke
 extern "C" size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype) {
   (void)hkv; (void)d; (void)dtype;
   if (!plan || hq <= 0) return 0;
-  size_t n = (size_t)hq * (size_t)plan->total_tokens * sizeof(float);  // delta [Hq,T], then lse2 [Hq,T]
+  size_t n = (size_t)hq * (size_t)plan->q_rows * sizeof(float);  // delta [Hq, rows], then lse2 [Hq, rows]
   n = (n + 255) & ~(size_t)255;
   return 2 * n;
 }
@@ -201,7 +201,7 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
   {
     ProfScope ps(DCP_K_DELTA, s);
     if ((st = stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
-                           t->lse, lse2, plan->total_tokens, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;
+                           t->lse, lse2, plan->q_rows, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;
   }
   {
     ProfScope ps(DCP_K_DQ, s);

@@ -41,13 +41,17 @@ struct DevGroup {
   const int32_t* ent_kind;   // [nnz]
   const int32_t* blk_start;  // [n_blocks]
   const int32_t* blk_len;    // [n_blocks]
+  // Block buffers (Sec. 5): a token's row in memory is its packed index plus the offset of its block,
+  // slot * block_size - blk_start (0 for packed tensors).
+  const int32_t* unit_moff;  // [n_units] offset of the unit's own block (Q side for fwd / dQ, KV side for dK/dV)
+  const int32_t* ent_moff;   // [nnz]     offset of each row's other block
   const WorkItem* items;     // [n_items] longest first
   int32_t n_items;
   int32_t n_units;
 };
 
 struct HostGroup {
-  std::vector<int32_t> unit_blk, unit_out, ptr, idx, ent_start, ent_len, ent_kind;
+  std::vector<int32_t> unit_blk, unit_out, ptr, idx, ent_blk, ent_start, ent_len, ent_kind;
 };
 
 struct DevItems {
@@ -61,6 +65,10 @@ struct dcp_plan {
   int32_t n_seq = 0, block_size = 0, n_blocks = 0, n_slots = 0;
   int64_t total_tokens = 0, n_kept = 0;
   bool use_slots = false, has_ranges = false;
+  // block buffers: slot of every block in the Q-type and the KV-type buffer (-1: absent), rows per buffer
+  bool buffers = false;
+  std::vector<int32_t> q_slot, kv_slot, q_moff, kv_moff;
+  int64_t q_rows = 0, kv_rows = 0;
   std::vector<int32_t> cu, blk_start, blk_len, blk_seq;
   std::vector<int32_t> table;  // original rows [n,3]
   std::vector<int32_t> slot_qblk, merge_ptr, merge_idx;
@@ -71,7 +79,7 @@ struct dcp_plan {
   int device = -1;
   int32_t* dev_arena = nullptr;
   dcp::DevGroup d_fwd{}, d_bwdq{}, d_bwdkv{};
-  const int32_t *d_merge_ptr = nullptr, *d_merge_idx = nullptr, *d_slot_qblk = nullptr;
+  const int32_t *d_merge_ptr = nullptr, *d_merge_idx = nullptr, *d_slot_qblk = nullptr, *d_q_mem0 = nullptr;
   std::map<std::pair<int, int>, dcp::DevItems> items;  // (group id, tile rows) -> work list
 
   dcp_status_t ensure_device(hipStream_t stream);

@@ -13,7 +13,7 @@ struct KTensors {
   const float* lse2;       // backward input [Hq,T]: max(lse * log2(e), -FLT_MAX), made by the preprocess
   const int32_t* ranges;   // [T,4] or null
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh, dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
-  int64_t total_tokens;
+  int64_t q_rows;   // rows of the Q-type buffers (= packed tokens without block buffers): row pitch of lse / delta / lse2
   int32_t hq, hkv, d, block_size;
   float scale;
   int32_t use_slots;
@@ -46,7 +46,7 @@ dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s);
 
 // streaming (HBM-bound) kernels
-dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, const int32_t* blk_start,
+dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, const int32_t* blk_mem0,
                           const int32_t* blk_len, int32_t n_blocks, int32_t block_size, const void* o_part,
                           const float* lse_part, void* out, int64_t o_st, int64_t o_sh, float* lse,
                           int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s);

@@ -71,6 +71,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
   const int blk_start = uni(g.blk_start[qb]), blk_len = uni(g.blk_len[qb]);
+  const int qoff = uni(g.unit_moff[w.unit]);   // rows of the Q-type buffers: packed index + qoff
   const int row0 = w.tile * TM;
   const int n_rows = min(TM, blk_len - row0);
   const int q_lo = blk_start + row0, q_hi = q_lo + n_rows - 1;
@@ -114,15 +115,15 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
     }
   }
   {
-    const bf16_t* qp = (const bf16_t*)t.q + (int64_t)st.qi * t.q_st + (int64_t)head * t.q_sh + 8 * lh;
-    const bf16_t* dop = (const bf16_t*)t.dout + (int64_t)st.qi * t.do_st + (int64_t)head * t.do_sh + 8 * lh;
+    const bf16_t* qp = (const bf16_t*)t.q + (int64_t)(st.qi + qoff) * t.q_st + (int64_t)head * t.q_sh + 8 * lh;
+    const bf16_t* dop = (const bf16_t*)t.dout + (int64_t)(st.qi + qoff) * t.do_st + (int64_t)head * t.do_sh + 8 * lh;
 #pragma unroll
     for (int ks = 0; ks < 8; ks++) {
       st.qf[ks] = as_frag(*(const uint4*)(qp + 16 * ks));
       st.dof[ks] = as_frag(*(const uint4*)(dop + 16 * ks));
     }
-    st.lse2 = t.lse2[(int64_t)head * t.total_tokens + st.qi];
-    st.delta = t.delta[(int64_t)head * t.total_tokens + st.qi];
+    st.lse2 = t.lse2[(int64_t)head * t.q_rows + st.qi + qoff];
+    st.delta = t.delta[(int64_t)head * t.q_rows + st.qi + qoff];
 #pragma unroll
     for (int dt = 0; dt < 4; dt++)
 #pragma unroll
@@ -135,8 +136,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   KvIter it(g, w.unit);
   bool have = it.next(q_hi, rb);
   if (have) {
-    st.dmak.load(stage0, kbase, it.ks, it.c1 - 1, wave);
-    st.dmav.load(stage0 + kTileBytes, vbase, it.ks, it.c1 - 1, wave);
+    st.dmak.load(stage0, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
+    st.dmav.load(stage0 + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
   }
   DCP_WAIT_VMCNT(0);
   __syncthreads();
@@ -144,8 +145,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
     have = it.next(q_hi, rb);
     if (have) {
-      st.dmak.load(nxt, kbase, it.ks, it.c1 - 1, wave);
-      st.dmav.load(nxt + kTileBytes, vbase, it.ks, it.c1 - 1, wave);
+      st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
+      st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
     }
     if (w_rows > 0) {
 #pragma unroll
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
     step(stage1, stage0);
   }
   if (!qv) return;
-  bf16_t* op = (bf16_t*)t.dq + (int64_t)st.qi * t.dq_st + (int64_t)head * t.dq_sh;
+  bf16_t* op = (bf16_t*)t.dq + (int64_t)(st.qi + qoff) * t.dq_st + (int64_t)head * t.dq_sh;
 #pragma unroll
   for (int dt = 0; dt < 4; dt++)
 #pragma unroll
@@ -184,12 +185,13 @@ static constexpr int kStageBytes = kStageRanges + 1024;
 
 // Walks (table row, query head of the group, 64-query tile) for one KV tile.
 struct QIter {
-  const int32_t *ent_start, *ent_len, *ent_kind;
+  const int32_t *ent_start, *ent_len, *ent_kind, *ent_moff;
   int e, e_end, hh, G, jt, n_t, jt0;
   int q0, q1, kind;
-  int qs;  // first query of the current tile
-  __device__ QIter(const DevGroup& g, int unit, int G_) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind) {
-    e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; qs = 0;
+  int moff;  // the Q block's rows sit at (packed index + moff) in the Q-type buffers
+  int qs;    // first query of the current tile
+  __device__ QIter(const DevGroup& g, int unit, int G_) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind), ent_moff(g.ent_moff) {
+    e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; moff = 0; qs = 0;
   }
   // k_lo: first key of the workgroup's tile.  Under CAUSAL, query tiles that end before k_lo see nothing.
   __device__ bool next(int k_lo) {
@@ -201,7 +203,7 @@ struct QIter {
           e++;
           if (e >= e_end) return false;
           hh = 0;
-          q0 = uni(ent_start[e]); q1 = q0 + uni(ent_len[e]); kind = uni(ent_kind[e]);
+          q0 = uni(ent_start[e]); q1 = q0 + uni(ent_len[e]); kind = uni(ent_kind[e]); moff = uni(ent_moff[e]);
           n_t = (q1 - q0 + kTN - 1) / kTN;
           jt0 = kind == 1 ? max(0, (k_lo - q0) / kTN) : 0;
         }
@@ -331,6 +333,7 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
   const int blk_start = uni(g.blk_start[kb]), blk_len = uni(g.blk_len[kb]);
+  const int koff = uni(g.unit_moff[w.unit]);   // rows of the KV-type buffers: packed index + koff
   const int row0 = w.tile * TK;
   const int n_rows = min(TK, blk_len - row0);
   const int k_lo = blk_start + row0, k_end = k_lo + n_rows;
@@ -346,8 +349,8 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   st.kj = k_lo + wrow0 + li;                       // may lie past k_end: masked, never stored
   {
     const int kl = min(st.kj, k_end - 1);
-    const bf16_t* kp = (const bf16_t*)t.k + (int64_t)kl * t.k_st + (int64_t)hk * t.k_sh + 8 * lh;
-    const bf16_t* vp = (const bf16_t*)t.v + (int64_t)kl * t.v_st + (int64_t)hk * t.v_sh + 8 * lh;
+    const bf16_t* kp = (const bf16_t*)t.k + (int64_t)(kl + koff) * t.k_st + (int64_t)hk * t.k_sh + 8 * lh;
+    const bf16_t* vp = (const bf16_t*)t.v + (int64_t)(kl + koff) * t.v_st + (int64_t)hk * t.v_sh + 8 * lh;
 #pragma unroll
     for (int ks = 0; ks < 8; ks++) {
       st.kf[ks] = as_frag(*(const uint4*)(kp + 16 * ks));
@@ -364,11 +367,12 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   auto issue = [&](char* stage) {
     const int head = hk * G + it.hh;
     const int last = it.q1 - 1;
-    st.dmaq.load(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, it.qs, last, wave);
-    st.dmao.load(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, it.qs, last, wave);
-    const int qrow = min(it.qs + lane, last);
-    if (wave == 0) dma4((unsigned)qrow * 4u, uni_ptr(t.lse2 + (int64_t)head * t.total_tokens), lds_addr(stage + kStageLse));
-    if (wave == 1) dma4((unsigned)qrow * 4u, uni_ptr(t.delta + (int64_t)head * t.total_tokens), lds_addr(stage + kStageDelta));
+    st.dmaq.load(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, it.qs + it.moff, last + it.moff, wave);
+    st.dmao.load(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, it.qs + it.moff, last + it.moff, wave);
+    const int qrow = min(it.qs + lane, last);   // packed index: the range array is not a data block
+    const int qmem = qrow + it.moff;
+    if (wave == 0) dma4((unsigned)qmem * 4u, uni_ptr(t.lse2 + (int64_t)head * t.q_rows), lds_addr(stage + kStageLse));
+    if (wave == 1) dma4((unsigned)qmem * 4u, uni_ptr(t.delta + (int64_t)head * t.q_rows), lds_addr(stage + kStageDelta));
     if (wave == 2 && it.kind == 2) dma16((unsigned)qrow * 16u, uni_ptr(t.ranges), lds_addr(stage + kStageRanges));
   };
   bool have = it.next(k_lo);
@@ -400,8 +404,8 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
     step(stage1, stage0);
   }
   if (!kvalid) return;
-  bf16_t* dkp = (bf16_t*)t.dk + (int64_t)st.kj * t.dk_st + (int64_t)hk * t.dk_sh;
-  bf16_t* dvp = (bf16_t*)t.dv + (int64_t)st.kj * t.dv_st + (int64_t)hk * t.dv_sh;
+  bf16_t* dkp = (bf16_t*)t.dk + (int64_t)(st.kj + koff) * t.dk_st + (int64_t)hk * t.dk_sh;
+  bf16_t* dvp = (bf16_t*)t.dv + (int64_t)(st.kj + koff) * t.dv_st + (int64_t)hk * t.dv_sh;
 #pragma unroll
   for (int dt = 0; dt < 4; dt++)
 #pragma unroll

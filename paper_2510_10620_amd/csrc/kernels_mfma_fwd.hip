@@ -196,6 +196,7 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
   const int blk_start = uni(g.blk_start[qb]), blk_len = uni(g.blk_len[qb]);
+  const int qoff = uni(g.unit_moff[w.unit]);          // rows of the Q-type buffers: packed index + qoff
   const int row0 = w.tile * TM;                       // first row of the tile inside the block
   const int n_rows = min(TM, blk_len - row0);         // valid rows of the tile (>= 1)
   const int q_lo = blk_start + row0, q_hi = q_lo + n_rows - 1;
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
   // Q fragments (B operand: lane = query column li, d = 16 ks + 8 lh ..)
 #pragma unroll
   for (int nq = 0; nq < NQ; nq++) {
-    const bf16_t* qp = (const bf16_t*)t.q + (int64_t)st.qi[nq] * t.q_st + (int64_t)head * t.q_sh + 8 * lh;
+    const bf16_t* qp = (const bf16_t*)t.q + (int64_t)(st.qi[nq] + qoff) * t.q_st + (int64_t)head * t.q_sh + 8 * lh;
 #pragma unroll
     for (int ks = 0; ks < 8; ks++) st.qf[nq][ks] = as_frag(*(const uint4*)(qp + 16 * ks));
     st.m[nq] = -INFINITY; st.l[nq] = 0.f;
@@ -262,8 +263,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
   KvIter it(g, w.unit);
   bool have = it.next(q_hi, rb);
   if (have) {
-    st.dmak.load(stage0, kbase, it.ks, it.c1 - 1, wave);
-    st.dmav.load(stage0 + kTileBytes, vbase, it.ks, it.c1 - 1, wave);
+    st.dmak.load(stage0, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
+    st.dmav.load(stage0 + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
   }
   DCP_WAIT_VMCNT(0);
   __syncthreads();
@@ -273,8 +274,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
     have = it.next(q_hi, rb);
     if (have) {
-      st.dmak.load(nxt, kbase, it.ks, it.c1 - 1, wave);
-      st.dmav.load(nxt + kTileBytes, vbase, it.ks, it.c1 - 1, wave);
+      st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
+      st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
     }
     if (w_rows > 0) {
       const int cls0 = classify32(kind, ks, c1, wq_lo, wq_hi, wrb), cls1 = classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb);
@@ -305,8 +306,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
     const int row = row0 + wrow0 + nq * 32 + li;  // row inside the block
     bf16_t* op;
     if (slot < 0) {
-      op = (bf16_t*)t.out + (int64_t)(blk_start + row) * t.o_st + (int64_t)head * t.o_sh;
-      if (lh == 0) t.lse[(int64_t)head * t.total_tokens + blk_start + row] = lse;
+      op = (bf16_t*)t.out + (int64_t)(blk_start + row + qoff) * t.o_st + (int64_t)head * t.o_sh;
+      if (lh == 0) t.lse[(int64_t)head * t.q_rows + blk_start + row + qoff] = lse;
     } else {
       op = (bf16_t*)t.out + (((int64_t)slot * t.block_size + row) * t.hq + head) * kD;
       if (lh == 0) t.lse[((int64_t)slot * t.hq + head) * t.block_size + row] = lse;

@@ -18,7 +18,8 @@ __global__ __launch_bounds__(kTile) void scalar_fwd_kernel(DevGroup g, KTensors 
   const int row = w.tile * kTile + threadIdx.x;
   const bool valid = row < g.blk_len[qb];
   const int i = g.blk_start[qb] + (valid ? row : 0);
-  const T* qp = (const T*)t.q + (int64_t)i * t.q_st + (int64_t)h * t.q_sh;
+  const int im = i + g.unit_moff[w.unit];   // the row's place in the Q-type buffers
+  const T* qp = (const T*)t.q + (int64_t)im * t.q_st + (int64_t)h * t.q_sh;
   float q[D], acc[D];
 #pragma unroll
   for (int d = 0; d < D; d++) { q[d] = Elem<T>::load(qp + d) * t.scale; acc[d] = 0.f; }
@@ -26,12 +27,12 @@ __global__ __launch_bounds__(kTile) void scalar_fwd_kernel(DevGroup g, KTensors 
   int4 r = make_int4(0, 0, 0, 0);
   if (t.ranges) r = ((const int4*)t.ranges)[i];
   for (int e = g.ptr[w.unit]; e < g.ptr[w.unit + 1]; e++) {
-    const int c0 = g.ent_start[e], c1 = c0 + g.ent_len[e], kind = g.ent_kind[e];
+    const int c0 = g.ent_start[e], c1 = c0 + g.ent_len[e], kind = g.ent_kind[e], km = g.ent_moff[e];
     for (int j = c0; j < c1; j++) {
       const bool vis = valid && key_visible(kind, i, j, r);
       if (!__any(vis)) continue;
-      const T* kp = (const T*)t.k + (int64_t)j * t.k_st + (int64_t)hk * t.k_sh;
-      const T* vp = (const T*)t.v + (int64_t)j * t.v_st + (int64_t)hk * t.v_sh;
+      const T* kp = (const T*)t.k + (int64_t)(j + km) * t.k_st + (int64_t)hk * t.k_sh;
+      const T* vp = (const T*)t.v + (int64_t)(j + km) * t.v_st + (int64_t)hk * t.v_sh;
       float s = 0.f;
 #pragma unroll
       for (int d = 0; d < D; d++) s = fmaf(q[d], Elem<T>::load(kp + d), s);
@@ -56,8 +57,8 @@ __global__ __launch_bounds__(kTile) void scalar_fwd_kernel(DevGroup g, KTensors 
   const int slot = g.unit_out[w.unit];
   T* op;
   if (slot < 0) {
-    op = (T*)t.out + (int64_t)i * t.o_st + (int64_t)h * t.o_sh;
-    t.lse[(int64_t)h * t.total_tokens + i] = lse;
+    op = (T*)t.out + (int64_t)im * t.o_st + (int64_t)h * t.o_sh;
+    t.lse[(int64_t)h * t.q_rows + im] = lse;
   } else {
     op = (T*)t.out + (((int64_t)slot * t.block_size + row) * t.hq + h) * D;
     t.lse[((int64_t)slot * t.hq + h) * t.block_size + row] = lse;
@@ -74,23 +75,24 @@ __global__ __launch_bounds__(kTile) void scalar_dq_kernel(DevGroup g, KTensors t
   const int row = w.tile * kTile + threadIdx.x;
   const bool valid = row < g.blk_len[qb];
   const int i = g.blk_start[qb] + (valid ? row : 0);
-  const T* qp = (const T*)t.q + (int64_t)i * t.q_st + (int64_t)h * t.q_sh;
-  const T* dop = (const T*)t.dout + (int64_t)i * t.do_st + (int64_t)h * t.do_sh;
+  const int im = i + g.unit_moff[w.unit];
+  const T* qp = (const T*)t.q + (int64_t)im * t.q_st + (int64_t)h * t.q_sh;
+  const T* dop = (const T*)t.dout + (int64_t)im * t.do_st + (int64_t)h * t.do_sh;
   float q[D], dO[D], dq[D];
 #pragma unroll
   for (int d = 0; d < D; d++) { q[d] = Elem<T>::load(qp + d) * t.scale; dO[d] = Elem<T>::load(dop + d); dq[d] = 0.f; }
-  const float lse = t.lse[(int64_t)h * t.total_tokens + i];
-  const float delta = t.delta[(int64_t)h * t.total_tokens + i];
+  const float lse = t.lse[(int64_t)h * t.q_rows + im];
+  const float delta = t.delta[(int64_t)h * t.q_rows + im];
   const bool row_on = valid && lse > -INFINITY;
   int4 r = make_int4(0, 0, 0, 0);
   if (t.ranges) r = ((const int4*)t.ranges)[i];
   for (int e = g.ptr[w.unit]; e < g.ptr[w.unit + 1]; e++) {
-    const int c0 = g.ent_start[e], c1 = c0 + g.ent_len[e], kind = g.ent_kind[e];
+    const int c0 = g.ent_start[e], c1 = c0 + g.ent_len[e], kind = g.ent_kind[e], km = g.ent_moff[e];
     for (int j = c0; j < c1; j++) {
       const bool vis = row_on && key_visible(kind, i, j, r);
       if (!__any(vis)) continue;
-      const T* kp = (const T*)t.k + (int64_t)j * t.k_st + (int64_t)hk * t.k_sh;
-      const T* vp = (const T*)t.v + (int64_t)j * t.v_st + (int64_t)hk * t.v_sh;
+      const T* kp = (const T*)t.k + (int64_t)(j + km) * t.k_st + (int64_t)hk * t.k_sh;
+      const T* vp = (const T*)t.v + (int64_t)(j + km) * t.v_st + (int64_t)hk * t.v_sh;
       float s = 0.f, dp = 0.f;
 #pragma unroll
       for (int d = 0; d < D; d++) {
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(kTile) void scalar_dq_kernel(DevGroup g, KTensors t
     }
   }
   if (!valid) return;
-  T* dqp = (T*)t.dq + (int64_t)i * t.dq_st + (int64_t)h * t.dq_sh;
+  T* dqp = (T*)t.dq + (int64_t)im * t.dq_st + (int64_t)h * t.dq_sh;
 #pragma unroll
   for (int d = 0; d < D; d++) Elem<T>::store(dqp + d, dq[d] * t.scale);
 }
@@ -119,23 +121,24 @@ __global__ __launch_bounds__(kTile) void scalar_dkv_kernel(DevGroup g, KTensors 
   const int row = w.tile * kTile + threadIdx.x;
   const bool valid = row < g.blk_len[kb];
   const int j = g.blk_start[kb] + (valid ? row : 0);
-  const T* kp = (const T*)t.k + (int64_t)j * t.k_st + (int64_t)hk * t.k_sh;
-  const T* vp = (const T*)t.v + (int64_t)j * t.v_st + (int64_t)hk * t.v_sh;
+  const int jm = j + g.unit_moff[w.unit];   // the row's place in the KV-type buffers
+  const T* kp = (const T*)t.k + (int64_t)jm * t.k_st + (int64_t)hk * t.k_sh;
+  const T* vp = (const T*)t.v + (int64_t)jm * t.v_st + (int64_t)hk * t.v_sh;
   float k[D], v[D], dk[D], dv[D];
 #pragma unroll
   for (int d = 0; d < D; d++) { k[d] = Elem<T>::load(kp + d); v[d] = Elem<T>::load(vp + d); dk[d] = 0.f; dv[d] = 0.f; }
   for (int hh = 0; hh < G; hh++) {
     const int h = hk * G + hh;
     for (int e = g.ptr[w.unit]; e < g.ptr[w.unit + 1]; e++) {
-      const int q0 = g.ent_start[e], q1 = q0 + g.ent_len[e], kind = g.ent_kind[e];
+      const int q0 = g.ent_start[e], q1 = q0 + g.ent_len[e], kind = g.ent_kind[e], qm = g.ent_moff[e];
       for (int i = q0; i < q1; i++) {
         int4 r = make_int4(0, 0, 0, 0);
         if (kind == 2) r = ((const int4*)t.ranges)[i];
-        const float lse = t.lse[(int64_t)h * t.total_tokens + i];
+        const float lse = t.lse[(int64_t)h * t.q_rows + i + qm];
         const bool vis = valid && lse > -INFINITY && key_visible(kind, i, j, r);
         if (!__any(vis)) continue;
-        const T* qp = (const T*)t.q + (int64_t)i * t.q_st + (int64_t)h * t.q_sh;
-        const T* dop = (const T*)t.dout + (int64_t)i * t.do_st + (int64_t)h * t.do_sh;
+        const T* qp = (const T*)t.q + (int64_t)(i + qm) * t.q_st + (int64_t)h * t.q_sh;
+        const T* dop = (const T*)t.dout + (int64_t)(i + qm) * t.do_st + (int64_t)h * t.do_sh;
         float s = 0.f, dp = 0.f;
 #pragma unroll
         for (int d = 0; d < D; d++) {
@@ -144,7 +147,7 @@ __global__ __launch_bounds__(kTile) void scalar_dkv_kernel(DevGroup g, KTensors 
         }
         if (vis) {
           const float p = expf(s * t.scale - lse);
-          const float ds = p * (dp - t.delta[(int64_t)h * t.total_tokens + i]) * t.scale;
+          const float ds = p * (dp - t.delta[(int64_t)h * t.q_rows + i + qm]) * t.scale;
 #pragma unroll
           for (int d = 0; d < D; d++) {
             dv[d] = fmaf(p, Elem<T>::load(dop + d), dv[d]);
@@ -155,8 +158,8 @@ __global__ __launch_bounds__(kTile) void scalar_dkv_kernel(DevGroup g, KTensors 
     }
   }
   if (!valid) return;
-  T* dkp = (T*)t.dk + (int64_t)j * t.dk_st + (int64_t)hk * t.dk_sh;
-  T* dvp = (T*)t.dv + (int64_t)j * t.dv_st + (int64_t)hk * t.dv_sh;
+  T* dkp = (T*)t.dk + (int64_t)jm * t.dk_st + (int64_t)hk * t.dk_sh;
+  T* dvp = (T*)t.dv + (int64_t)jm * t.dv_st + (int64_t)hk * t.dv_sh;
 #pragma unroll
   for (int d = 0; d < D; d++) { Elem<T>::store(dkp + d, dk[d]); Elem<T>::store(dvp + d, dv[d]); }
 }

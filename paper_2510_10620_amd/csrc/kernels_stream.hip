@@ -39,13 +39,15 @@ static constexpr int kMergeRows = 4;
 
 template <typename T>
 __global__ __launch_bounds__(256) void merge_kernel(const int32_t* __restrict__ merge_ptr, const int32_t* __restrict__ merge_idx,
-                                                    const int32_t* __restrict__ blk_start, const int32_t* __restrict__ blk_len,
+                                                    const int32_t* __restrict__ blk_mem0, const int32_t* __restrict__ blk_len,
                                                     int32_t block_size, const T* __restrict__ o_part,
                                                     const float* __restrict__ lse_part, T* __restrict__ out, int64_t o_st,
-                                                    int64_t o_sh, float* __restrict__ lse, int64_t total_tokens, int32_t hq,
+                                                    int64_t o_sh, float* __restrict__ lse, int64_t q_rows, int32_t hq,
                                                     int32_t d) {
   const int b = blockIdx.y;
   const int len = blk_len[b];
+  const int mem0 = blk_mem0[b];   // the block's first row in out / lse; negative: the block is not in the buffer
+  if (mem0 < 0) return;
   const int row0 = blockIdx.x * kMergeRows;
   if (row0 >= len) return;
   const int p0 = merge_ptr[b], p1 = merge_ptr[b + 1];
@@ -73,23 +75,23 @@ __global__ __launch_bounds__(256) void merge_kernel(const int32_t* __restrict__ 
 #pragma unroll
       for (int i = 0; i < 8; i++) acc[i] *= inv;
     }
-    const int64_t tok = (int64_t)blk_start[b] + row;
+    const int64_t tok = (int64_t)mem0 + row;
     Vec8<T>::store(out + tok * o_st + (int64_t)h * o_sh + c * 8, acc);
-    if (c == 0) lse[(int64_t)h * total_tokens + tok] = m > -INFINITY ? m + logf(tot) : -INFINITY;
+    if (c == 0) lse[(int64_t)h * q_rows + tok] = m > -INFINITY ? m + logf(tot) : -INFINITY;
   }
 }
 
-dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, const int32_t* blk_start,
+dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, const int32_t* blk_mem0,
                           const int32_t* blk_len, int32_t n_blocks, int32_t block_size, const void* o_part,
                           const float* lse_part, void* out, int64_t o_st, int64_t o_sh, float* lse,
                           int64_t total_tokens, int32_t hq, int32_t d, int32_t dtype, hipStream_t s) {
   if (n_blocks == 0) return DCP_OK;
   dim3 grid((block_size + kMergeRows - 1) / kMergeRows, n_blocks), block(256);
   if (dtype == DCP_BF16)
-    hipLaunchKernelGGL(merge_kernel<bf16_t>, grid, block, 0, s, merge_ptr, merge_idx, blk_start, blk_len, block_size,
+    hipLaunchKernelGGL(merge_kernel<bf16_t>, grid, block, 0, s, merge_ptr, merge_idx, blk_mem0, blk_len, block_size,
                        (const bf16_t*)o_part, lse_part, (bf16_t*)out, o_st, o_sh, lse, total_tokens, hq, d);
   else
-    hipLaunchKernelGGL(merge_kernel<float>, grid, block, 0, s, merge_ptr, merge_idx, blk_start, blk_len, block_size,
+    hipLaunchKernelGGL(merge_kernel<float>, grid, block, 0, s, merge_ptr, merge_idx, blk_mem0, blk_len, block_size,
                        (const float*)o_part, lse_part, (float*)out, o_st, o_sh, lse, total_tokens, hq, d);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;

@@ -138,12 +138,14 @@ static void build_group(const dcp_plan& pl, const std::vector<int64_t>& kept, in
   for (int64_t e : order) g->ptr[unit_of(e) + 1]++;
   for (int32_t u = 0; u < n_units; u++) g->ptr[u + 1] += g->ptr[u];
   g->idx.clear();
+  g->ent_blk.clear();
   g->ent_start.clear();
   g->ent_len.clear();
   g->ent_kind.clear();
   for (int64_t e : order) {
     int32_t ob = other_of(e);
     g->idx.push_back((int32_t)e);
+    g->ent_blk.push_back(ob);
     g->ent_start.push_back(pl.blk_start[ob]);
     g->ent_len.push_back(pl.blk_len[ob]);
     g->ent_kind.push_back(pl.table[3 * e + 2]);
@@ -167,6 +169,9 @@ extern "C" dcp_status_t dcp_plan_create(dcp_plan_t** out, const int32_t* cu, int
   pl->block_size = B;
   pl->n_blocks = (int32_t)p.start.size();
   pl->total_tokens = n_seq > 0 ? cu[n_seq] : 0;
+  pl->q_rows = pl->kv_rows = pl->total_tokens;
+  pl->q_moff.assign(pl->n_blocks, 0);
+  pl->kv_moff.assign(pl->n_blocks, 0);
   pl->cu.assign(cu, cu + (n_seq > 0 ? n_seq + 1 : 0));
   pl->blk_start = p.start;
   pl->blk_len = p.len;
@@ -236,6 +241,51 @@ extern "C" dcp_status_t dcp_plan_create(dcp_plan_t** out, const int32_t* cu, int
   return DCP_OK;
 }
 
+extern "C" dcp_status_t dcp_plan_set_block_buffers(dcp_plan_t* plan, const int32_t* q_slot, int32_t n_q_slots,
+                                                   const int32_t* kv_slot, int32_t n_kv_slots) {
+  if (!plan) return fail(DCP_ERR_INVALID_ARG, "plan is NULL");
+  std::lock_guard<std::mutex> lock(plan->mu);
+  if (plan->dev_arena) return fail(DCP_ERR_INVALID_ARG, "block buffers must be set before the plan is first used on a device");
+  if (plan->n_blocks > 0 && (!q_slot || !kv_slot)) return fail(DCP_ERR_INVALID_ARG, "slot array is NULL");
+  if (n_q_slots < 0 || n_kv_slots < 0) return fail(DCP_ERR_INVALID_ARG, "negative slot count");
+  const int64_t B = plan->block_size;
+  if ((int64_t)n_q_slots * B > INT32_MAX || (int64_t)n_kv_slots * B > INT32_MAX)
+    return fail(DCP_ERR_INVALID_ARG, "a block buffer would hold 2^31 rows or more");
+  std::vector<char> used_q(plan->n_blocks, 0), used_kv(plan->n_blocks, 0);
+  for (size_t e = 0; e + 2 < plan->table.size(); e += 3) {
+    if (plan->table[e + 2] == DCP_MASK_SKIP) continue;
+    used_q[plan->table[e]] = 1;
+    used_kv[plan->table[e + 1]] = 1;
+  }
+  for (int side = 0; side < 2; side++) {
+    const int32_t* slot = side ? kv_slot : q_slot;
+    const int32_t n = side ? n_kv_slots : n_q_slots;
+    const std::vector<char>& used = side ? used_kv : used_q;
+    std::vector<char> taken(n, 0);
+    for (int32_t b = 0; b < plan->n_blocks; b++) {
+      const int32_t s = slot[b];
+      const std::string what = std::string(side ? "kv" : "q") + " slot of block " + std::to_string(b);
+      if (s < -1 || s >= n) return fail(DCP_ERR_BAD_TABLE, what + " is out of range");
+      if (s < 0) {
+        if (used[b]) return fail(DCP_ERR_BAD_TABLE, what + " is absent but the table uses the block");
+        continue;
+      }
+      if (taken[s]) return fail(DCP_ERR_BAD_TABLE, what + " is taken by another block");
+      taken[s] = 1;
+    }
+  }
+  plan->buffers = true;
+  plan->q_slot.assign(q_slot, q_slot + plan->n_blocks);
+  plan->kv_slot.assign(kv_slot, kv_slot + plan->n_blocks);
+  for (int32_t b = 0; b < plan->n_blocks; b++) {
+    plan->q_moff[b] = q_slot[b] < 0 ? 0 : (int32_t)((int64_t)q_slot[b] * B - plan->blk_start[b]);
+    plan->kv_moff[b] = kv_slot[b] < 0 ? 0 : (int32_t)((int64_t)kv_slot[b] * B - plan->blk_start[b]);
+  }
+  plan->q_rows = (int64_t)n_q_slots * B;
+  plan->kv_rows = (int64_t)n_kv_slots * B;
+  return DCP_OK;
+}
+
 extern "C" dcp_status_t dcp_plan_destroy(dcp_plan_t* plan) {
   if (!plan) return DCP_OK;
   if (plan->dev_arena || !plan->items.empty()) {
@@ -296,11 +346,24 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     return off;
   };
   size_t o_bs = put(blk_start), o_bl = put(blk_len);
-  struct Off { size_t ub, uo, ptr, es, el, ek; } go[3];
+  struct Off { size_t ub, uo, ptr, es, el, ek, um, em; } go[3];
   HostGroup* gs[3] = {&fwd, &bwdq, &bwdkv};
-  for (int i = 0; i < 3; i++)
-    go[i] = {put(gs[i]->unit_blk), put(gs[i]->unit_out), put(gs[i]->ptr), put(gs[i]->ent_start), put(gs[i]->ent_len), put(gs[i]->ent_kind)};
+  for (int i = 0; i < 3; i++) {
+    // memory offsets: own side = Q for the query-side groups, KV for the dK/dV group
+    const std::vector<int32_t>& own = i == 2 ? kv_moff : q_moff;
+    const std::vector<int32_t>& other = i == 2 ? q_moff : kv_moff;
+    std::vector<int32_t> um(gs[i]->unit_blk.size(), 0), em(gs[i]->ent_blk.size(), 0);
+    for (size_t u = 0; u < um.size(); u++)
+      if (gs[i]->unit_blk[u] >= 0) um[u] = own[gs[i]->unit_blk[u]];
+    for (size_t e = 0; e < em.size(); e++) em[e] = other[gs[i]->ent_blk[e]];
+    go[i] = {put(gs[i]->unit_blk), put(gs[i]->unit_out), put(gs[i]->ptr), put(gs[i]->ent_start), put(gs[i]->ent_len), put(gs[i]->ent_kind),
+             put(um), put(em)};
+  }
   size_t o_mp = put(merge_ptr), o_mi = put(merge_idx), o_sq = put(slot_qblk);
+  // first row of every block in the Q-type buffers (-1: absent), for the merge
+  std::vector<int32_t> q_mem0(n_blocks);
+  for (int32_t b = 0; b < n_blocks; b++) q_mem0[b] = (buffers && q_slot[b] < 0) ? -1 : blk_start[b] + q_moff[b];
+  size_t o_qm = put(q_mem0);
   host.push_back(0);
   DCP_HIP_TRY(hipMalloc((void**)&dev_arena, host.size() * sizeof(int32_t)));
   hipError_t e = hipMemcpyAsync(dev_arena, host.data(), host.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream);
@@ -319,6 +382,8 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     ds[i]->ent_start = dev_arena + go[i].es;
     ds[i]->ent_len = dev_arena + go[i].el;
     ds[i]->ent_kind = dev_arena + go[i].ek;
+    ds[i]->unit_moff = dev_arena + go[i].um;
+    ds[i]->ent_moff = dev_arena + go[i].em;
     ds[i]->blk_start = dev_arena + o_bs;
     ds[i]->blk_len = dev_arena + o_bl;
     ds[i]->items = nullptr;
@@ -328,6 +393,7 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
   d_merge_ptr = dev_arena + o_mp;
   d_merge_idx = dev_arena + o_mi;
   d_slot_qblk = dev_arena + o_sq;
+  d_q_mem0 = dev_arena + o_qm;
   return DCP_OK;
 }
 
@@ -360,6 +426,7 @@ dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, Dev
     for (int32_t u = 0; u < (int32_t)hg->unit_blk.size(); u++) {
       int32_t b = hg->unit_blk[u];
       if (b < 0) continue;  // unused slot
+      if (buffers && (gid == 2 ? kv_slot[b] : q_slot[b]) < 0) continue;  // block absent from its buffer: nothing to write
       int32_t nt = (blk_len[b] + tile_rows - 1) / tile_rows;
       for (int32_t t = 0; t < nt; t++) {
         int64_t r0 = blk_start[b] + (int64_t)t * tile_rows;

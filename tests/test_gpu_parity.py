@@ -227,3 +227,98 @@ def test_blockwise_copy_bit_exact():
         P.dcp_blockwise_copy(bad, tbuf, tbuf)
     # an empty list does nothing
     P.dcp_blockwise_copy(P.CopyList(np.zeros((0, 3), np.int32), T, n_slots * B), tx, tbuf)
+
+
+def _buffer_case(w, table, impl, rng, absent_ok=False, out_slot=None, n_slots=0):
+    """Runs forward + backward with every tensor held in block buffers (permuted slots, free slots in
+    between, unused rows poisoned) and compares what comes back, block by block, with the oracle on the
+    packed tensors.  Returns nothing; asserts."""
+    import torch
+    import paper_2510_10620_amd as P
+    from oracle import blockbuf as BB
+    tensors = W.make_tensors(w)
+    table = np.asarray(table, dtype=np.int32).reshape(-1, 3)
+    part = OB.block_partition(w.cu_seqlens, w.block_size)
+    bs, bl = part["blk_start"], part["blk_end"] - part["blk_start"]
+    nb, B, T = len(bs), w.block_size, w.total_tokens
+    live = table[table[:, 2] != 3]
+    used_q, used_kv = np.zeros(nb, bool), np.zeros(nb, bool)
+    used_q[live[:, 0]] = True
+    used_kv[live[:, 1]] = True
+    n_qs, n_ks = nb + 2, nb + 3
+    q_slot = rng.permutation(n_qs)[:nb].astype(np.int32)
+    kv_slot = rng.permutation(n_ks)[:nb].astype(np.int32)
+    if absent_ok:
+        q_slot[~used_q] = -1
+        kv_slot[~used_kv] = -1
+    plan = P.dcp_plan_create(w.cu_seqlens, B, table, out_slot, n_slots)
+    P.dcp_plan_set_block_buffers(plan, q_slot, n_qs, kv_slot, n_ks)
+    nan16 = np.uint16(0x7FC0)
+    fill = nan16 if w.dtype == "bf16" else np.float32("nan")
+    buf = {n: BB.gather_blocks(tensors[n], bs, bl, q_slot if n in ("q", "dout") else kv_slot,
+                               n_qs if n in ("q", "dout") else n_ks, B, fill=fill) for n in ("q", "k", "v", "dout")}
+    tq, tk, tv, tdo = (H.to_torch(w, buf[n]) for n in ("q", "k", "v", "dout"))
+    rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+    out = torch.full((n_qs * B, w.hq, w.d), 768.0, dtype=tq.dtype, device="cuda")
+    lse = torch.full((w.hq, n_qs * B), 768.0, dtype=torch.float32, device="cuda")
+    if out_slot is not None:
+        o_part = torch.full((n_slots, B, w.hq, w.d), float("nan"), dtype=tq.dtype, device="cuda")
+        lse_part = torch.full((n_slots, w.hq, B), float("nan"), dtype=torch.float32, device="cuda")
+        P.dcp_block_attn_fwd(plan, tq, tk, tv, o_part, lse_part, w.softmax_scale, rg, impl)
+        P.dcp_merge_partials(plan, o_part, lse_part, out, lse)
+    else:
+        P.dcp_block_attn_fwd(plan, tq, tk, tv, out, lse, w.softmax_scale, rg, impl)
+    dq = torch.full_like(out, 768.0)
+    dk = torch.full((n_ks * B, w.hkv, w.d), 768.0, dtype=tq.dtype, device="cuda")
+    dv = torch.full_like(dk, 768.0)
+    ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plan, w.hq, w.hkv, w.d, P.DCP_BF16 if w.dtype == "bf16" else P.DCP_F32)),
+                     dtype=torch.uint8, device="cuda")
+    ref = H.oracle_full(w, tensors, table)
+    # the backward takes the forward's out / lse when the table is complete; for a share, the oracle's global ones
+    P.dcp_block_attn_bwd(plan, tq, tk, tv, out, lse, tdo, dq, dk, dv, w.softmax_scale, ws, rg, impl)
+    torch.cuda.synchronize()
+    got_buf = dict(out=H.from_torch(out), dq=H.from_torch(dq), dk=H.from_torch(dk), dv=H.from_torch(dv))
+    got = {n: BB.scatter_blocks(got_buf[n], bs, bl, q_slot if n in ("out", "dq") else kv_slot, B, T) for n in got_buf}
+    got["lse"] = BB.scatter_rows_hT(H.from_torch(lse), bs, bl, q_slot, B, T)
+    # blocks that are absent from a buffer have no result: compare the oracle's zeros / -inf there with what
+    # scatter leaves (zeros), except lse, which scatter also leaves at 0
+    for n, slot in (("out", q_slot), ("dq", q_slot), ("dk", kv_slot), ("dv", kv_slot), ("lse", q_slot)):
+        for b in np.nonzero(slot < 0)[0]:
+            sl = slice(bs[b], bs[b] + bl[b])
+            if n == "lse":
+                ref[n][:, sl] = 0.0
+            else:
+                assert not np.abs(ref[n][sl]).max() > 0, "a block the table uses was declared absent"
+    H.check(w, got, ref, ALL, "block buffers")
+    # rows no block owns keep the sentinel
+    for n, slot, rows in (("out", q_slot, n_qs * B), ("dq", q_slot, n_qs * B), ("dk", kv_slot, n_ks * B), ("dv", kv_slot, n_ks * B)):
+        owned = np.zeros(rows, bool)
+        for b in range(nb):
+            if slot[b] >= 0:
+                owned[slot[b] * B: slot[b] * B + bl[b]] = True
+        assert (got_buf[n][~owned] == 768.0).all(), n + ": a row outside every block was written"
+
+
+@pytest.mark.parametrize("impl", list(IMPLS), ids=list(IMPLS))
+def test_block_buffer_addressing(impl):
+    """Sec. 5: Q / KV / O blocks addressed through block buffers (slot * block_size + row) give what the packed
+    tensors give.  Causal and lambda masks (NONE, CAUSAL and RANGES rows), ragged last blocks, blocks spanning
+    several kernel tiles."""
+    rng = np.random.default_rng(42)
+    w = W.custom_workload("buf_causal", [300, 77, 520], 160, 4, 2, 128, "bf16", W.MaskSpec("causal"), seed=43, input_scale=0.5)
+    _buffer_case(w, H.oracle_table(w), IMPLS[impl], rng)
+    w = W.custom_workload("buf_lambda", [413, 90], 96, 4, 2, 128, "bf16", W.MaskSpec("lambda", window=130, sink=20), seed=44, input_scale=0.5)
+    _buffer_case(w, H.oracle_table(w), IMPLS[impl], rng)
+
+
+def test_block_buffer_with_absent_blocks_and_partial_slots():
+    """A window mask whose table leaves some blocks unused on one side is run with those blocks absent from the
+    buffer (slot -1), and with partial output slots merged into the Q-type buffer."""
+    rng = np.random.default_rng(45)
+    w = W.custom_workload("buf_slots", [400, 200], 64, 4, 4, 128, "bf16", W.MaskSpec("causal"), seed=46, input_scale=0.5)
+    table = H.oracle_table(w)
+    slot, n_slots, _ = W.deal_divisions(table[:, 0], 3, 5)
+    _buffer_case(w, table, 0, rng, out_slot=slot, n_slots=n_slots)
+    # drop every row that has q_blk 2 or kv_blk 5: block 2 produces no output, block 5 receives no gradient
+    sub = table[(table[:, 0] != 2) & (table[:, 1] != 5)]
+    _buffer_case(w, sub, 0, rng, absent_ok=True)

@@ -176,3 +176,28 @@ def test_copy_list_validation():
     assert _copy_err([[0, 2, 3]], 4, 4).status == P.DCP_ERR_BAD_TABLE          # writes past the destination
     assert _copy_err([[0, 0, 3], [4, 2, 2]], 8, 8).status == P.DCP_ERR_BAD_TABLE  # destinations overlap
     assert _copy_err([[0, 0, 1]], -1, 4).status == P.DCP_ERR_INVALID_ARG
+
+
+def test_block_buffer_slot_validation():
+    cu = np.array([0, 100, 150], dtype=np.int32)
+    table = OB.dense_causal_table(cu, 32)                 # 4 + 2 blocks
+    table = table[table[:, 0] >= table[:, 1]]
+    def plan():
+        return P.dcp_plan_create(cu, 32, table)
+    ok = np.arange(6, dtype=np.int32)
+    P.dcp_plan_set_block_buffers(plan(), ok[::-1].copy(), 6, ok, 9)
+    for q_slot, nq, kv_slot, nk in ((np.array([0, 1, 2, 3, 4, 6]), 6, ok, 6),      # out of range
+                                    (np.array([0, 1, 2, 3, 4, 4]), 6, ok, 6),      # two blocks in one slot
+                                    (ok, 6, np.array([0, 1, 2, 3, 4, -1]), 6),     # a used block is absent
+                                    (np.array([0, 1, 2, 3, 4, -2]), 6, ok, 6)):
+        with pytest.raises(P.DcpError) as e:
+            P.dcp_plan_set_block_buffers(plan(), np.asarray(q_slot, np.int32), nq, np.asarray(kv_slot, np.int32), nk)
+        assert e.value.status == P.DCP_ERR_BAD_TABLE
+    with pytest.raises(P.DcpError) as e:
+        P.dcp_plan_set_block_buffers(plan(), ok, -1, ok, 6)
+    assert e.value.status == P.DCP_ERR_INVALID_ARG
+    # a block no row uses may be absent
+    sub = table[(table[:, 0] != 5) & (table[:, 1] != 5)]
+    pl = P.dcp_plan_create(cu, 32, sub)
+    s5 = ok.copy(); s5[5] = -1
+    P.dcp_plan_set_block_buffers(pl, s5, 6, s5, 6)
