@@ -71,7 +71,7 @@ __device__ __forceinline__ void fwd_subtile(FwdState<NQ>& st, const char* k_lds,
 #pragma unroll
     for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[nq][r]), s[nq][r + 1]);
     mx = fmaxf(mx, s[nq][15]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = xhalf_max(mx);
     // The reference max m is raised only when the tile's max exceeds it by more than 2^kLazy
     // (in the exp2 domain): until then P = exp2(c (s - m)) stays below 2^kLazy, exact in fp32 and
     // bf16 range, and the accumulators need no rescaling.  O and l are divided by the same sum at
@@ -139,7 +139,7 @@ __device__ __forceinline__ void fwd_tile64(FwdState<NQ>& st, const char* k_lds, 
       mx = fmaxf(fmaxf(mx, s[0][nq][r]), s[0][nq][r + 1]);
       mx = fmaxf(fmaxf(mx, s[1][nq][r]), s[1][nq][r + 1]);
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = xhalf_max(mx);
     const bool raise = (mx - st.m[nq]) * c_log2 > kLazy;
     const float m_new = raise ? mx : st.m[nq];
     const float mc = m_new * c_log2;               // finite: a full tile has a finite max
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
   const int slot = g.unit_out[w.unit];
 #pragma unroll
   for (int nq = 0; nq < NQ; nq++) {
-    const float lt = st.l[nq] + __shfl_xor(st.l[nq], 32);
+    const float lt = xhalf_sum(st.l[nq]);
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const float lse = lt > 0.f ? (st.m[nq] * c_log2 + __builtin_amdgcn_logf(lt)) * 0.69314718055994530942f : -INFINITY;
     if (!qv[nq]) continue;

@@ -251,6 +251,19 @@ __device__ __forceinline__ int classify(int kind, int ks, int c1, int q_lo, int 
 
 __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Combine a value with the one held by lane (l ^ 32), in every lane, without an LDS round trip:
+// v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second, so
+// with the same value in both, each lane ends up holding the lower half's value in one result and
+// the upper half's in the other.
+__device__ __forceinline__ float xhalf_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Walks the (table row, key tile) pairs of a unit that the workgroup cannot skip.  All state is
 // wave-uniform.
 struct KvIter {
