@@ -185,6 +185,7 @@ def main():
     if not args.no_extra:
         extra["share"] = share_section(torch, P, W, np, steps=max(3, args.steps // 4), warmup=2)
         extra["blockwise_copy"] = copy_section(torch, P, np, plan, q, steps=max(3, args.steps // 2))
+        extra["other_masks"] = masks_section(torch, P, W, np, steps=3)
 
     # one plain copy of known size (256 MiB read + 256 MiB written) through the library's sum
     # kernel with a single part: the reference dispatch that scales hardware byte counters
@@ -264,6 +265,43 @@ def share_section(torch, P, W, np, steps, warmup):
         res[name + "_ms"] = round(tot / max(n, 1), 4)
     res["merge_GBps"] = round(merge_bytes / (res["merge_ms"] * 1e-3) / 1e9, 1)
     res["merge_frac_hbm"] = round(res["merge_GBps"] / PEAK_HBM_GBPS, 3)
+    return res
+
+
+def masks_section(torch, P, W, np, steps):
+    """The same step (forward + backward) on the other mask families of the paper at their full shapes: sliding
+    window (config 3), lambda (4), causal blockwise (6), shared question (7).  Not the headline metric."""
+    res = {}
+    for cfg in (3, 4, 6, 7):
+        w = W.make_workload(cfg)
+        table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+        pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, table, w.ranges).sum())
+        q, k, v, do = gen_tensors(torch, w, w.tensor_seed)
+        plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)
+        out = torch.empty_like(q)
+        lse = torch.empty((w.hq, w.total_tokens), dtype=torch.float32, device="cuda")
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+        ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plan, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
+
+        def step():
+            P.dcp_block_attn_fwd(plan, q, k, v, out, lse, w.softmax_scale, rg)
+            P.dcp_block_attn_bwd(plan, q, k, v, out, lse, do, dq, dk, dv, w.softmax_scale, ws, rg)
+
+        step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        kinds = np.bincount(table[:, 2], minlength=3)
+        res[w.name] = dict(tokens=int(w.total_tokens), table_rows=int(len(table)), rows_none_causal_ranges=[int(x) for x in kinds[:3]],
+                           visible_pairs=pairs, ms_per_step=round(ms, 3),
+                           tflops=round(14 * pairs * w.hq * w.d / (ms * 1e-3) / 1e12, 1))
+        del q, k, v, do, out, lse, dq, dk, dv, ws, plan
     return res
 
 

@@ -92,6 +92,7 @@ static KTensors pack(const dcp_plan_t* plan, const dcp_tensors_t* t) {
   k.out = t->out; k.dq = t->dq; k.dk = t->dk; k.dv = t->dv;
   k.lse = t->lse; k.delta = nullptr;
   k.ranges = plan->has_ranges ? t->attn_ranges : nullptr;   // kernels skip all range work when no row is RANGES
+  k.qbounds = nullptr;
   k.q_st = t->q_stride_t; k.q_sh = t->q_stride_h; k.k_st = t->k_stride_t; k.k_sh = t->k_stride_h;
   k.v_st = t->v_stride_t; k.v_sh = t->v_stride_h; k.o_st = t->o_stride_t; k.o_sh = t->o_stride_h;
   k.do_st = t->do_stride_t; k.do_sh = t->do_stride_h; k.dq_st = t->dq_stride_t; k.dq_sh = t->dq_stride_h;
@@ -165,7 +166,10 @@ extern "C" size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, in
   if (!plan || hq <= 0) return 0;
   size_t n = (size_t)hq * (size_t)plan->q_rows * sizeof(float);  // delta [Hq, rows], then lse2 [Hq, rows]
   n = (n + 255) & ~(size_t)255;
-  return 2 * n;
+  // range-bound summaries of every 32-row tile (+1 spare entry), only for tables with RANGES rows
+  size_t nb = plan->has_ranges ? ((size_t)plan->blk_t32.back() + 1) * 8 * sizeof(int32_t) : 0;
+  nb = (nb + 255) & ~(size_t)255;
+  return 2 * n + nb;
 }
 
 extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace,
@@ -194,10 +198,18 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
   if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &gq)) != DCP_OK) return st;
   if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv)) != DCP_OK) return st;
   KTensors k = pack(plan, t);
+  size_t n_hT = (size_t)t->hq * (size_t)plan->q_rows * sizeof(float);
+  n_hT = (n_hT + 255) & ~(size_t)255;
   float* delta = (float*)workspace;
-  float* lse2 = (float*)((char*)workspace + need / 2);
+  float* lse2 = (float*)((char*)workspace + n_hT);
   k.delta = delta;
   k.lse2 = lse2;
+  if (plan->has_ranges && use_mfma) {
+    int32_t* qb = (int32_t*)((char*)workspace + 2 * n_hT);
+    k.qbounds = qb;
+    if ((st = mfma_range_bounds(gkv.blk_start, gkv.blk_len, plan->d_blk_t32, plan->n_blocks, plan->block_size, t->attn_ranges, qb, s)) != DCP_OK)
+      return st;
+  }
   {
     ProfScope ps(DCP_K_DELTA, s);
     if ((st = stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,

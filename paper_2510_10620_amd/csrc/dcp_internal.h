@@ -45,6 +45,8 @@ struct DevGroup {
   // slot * block_size - blk_start (0 for packed tensors).
   const int32_t* unit_moff;  // [n_units] offset of the unit's own block (Q side for fwd / dQ, KV side for dK/dV)
   const int32_t* ent_moff;   // [nnz]     offset of each row's other block
+  const int32_t* ent_t32;    // [nnz]     index of the other block's first 32-row tile (range-bound summaries)
+  const int32_t* ent_rec;    // [nnz][8]  the same per row in one record: start, len, kind, moff, t32, 0, 0, 0 (32-byte aligned)
   const WorkItem* items;     // [n_items] longest first
   int32_t n_items;
   int32_t n_units;
@@ -69,6 +71,7 @@ struct dcp_plan {
   bool buffers = false;
   std::vector<int32_t> q_slot, kv_slot, q_moff, kv_moff;
   int64_t q_rows = 0, kv_rows = 0;
+  std::vector<int32_t> blk_t32;   // [n_blocks + 1] prefix sums of ceil(blk_len / 32)
   std::vector<int32_t> cu, blk_start, blk_len, blk_seq;
   std::vector<int32_t> table;  // original rows [n,3]
   std::vector<int32_t> slot_qblk, merge_ptr, merge_idx;
@@ -79,7 +82,7 @@ struct dcp_plan {
   int device = -1;
   int32_t* dev_arena = nullptr;
   dcp::DevGroup d_fwd{}, d_bwdq{}, d_bwdkv{};
-  const int32_t *d_merge_ptr = nullptr, *d_merge_idx = nullptr, *d_slot_qblk = nullptr, *d_q_mem0 = nullptr;
+  const int32_t *d_merge_ptr = nullptr, *d_merge_idx = nullptr, *d_slot_qblk = nullptr, *d_q_mem0 = nullptr, *d_blk_t32 = nullptr;
   std::map<std::pair<int, int>, dcp::DevItems> items;  // (group id, tile rows) -> work list
 
   dcp_status_t ensure_device(hipStream_t stream);

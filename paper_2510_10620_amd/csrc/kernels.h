@@ -12,6 +12,7 @@ struct KTensors {
   const float* delta;      // backward input [Hq,T]
   const float* lse2;       // backward input [Hq,T]: max(lse * log2(e), -FLT_MAX), made by the preprocess
   const int32_t* ranges;   // [T,4] or null
+  const int32_t* qbounds;  // backward, or null: [32-row tiles of all blocks + 1][8] bounds of the rows' ranges (RangeBounds order)
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh, dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
   int64_t q_rows;   // rows of the Q-type buffers (= packed tokens without block buffers): row pitch of lse / delta / lse2
   int32_t hq, hkv, d, block_size;
@@ -44,6 +45,9 @@ int mfma_dkv_tile();
 dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s);
+// per 32-row tile of every block: bounds of its rows' range arrays -> qbounds [n_t32 + 1][8]
+dcp_status_t mfma_range_bounds(const int32_t* blk_start, const int32_t* blk_len, const int32_t* blk_t32, int32_t n_blocks,
+                               int32_t block_size, const int32_t* ranges, int32_t* qbounds, hipStream_t s);
 
 // streaming (HBM-bound) kernels
 dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, const int32_t* blk_mem0,

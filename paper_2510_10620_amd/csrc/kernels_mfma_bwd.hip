@@ -181,20 +181,67 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
 static constexpr int kStageLse = 2 * kTileBytes;
 static constexpr int kStageDelta = kStageLse + 256;
 static constexpr int kStageRanges = kStageDelta + 256;
-static constexpr int kStageBytes = kStageRanges + 1024;
+static constexpr int kStageBounds = kStageRanges + 1024;   // range bounds of the tile's two 32-row halves (2 x 8 ints; 1 KB reserved)
+static constexpr int kStageBytes = kStageBounds + 1024;
+
+// Bounds of the range arrays of every 32-row tile of every block (rows of a tile = lanes 0..31), so that the
+// dK/dV kernel, which streams query tiles past fixed keys, can tell without reading the rows whether a tile
+// sees any of its keys (skip) or all of them (no per-element test).  Entry layout = RangeBounds member order.
+__global__ __launch_bounds__(256) void range_bounds_kernel(const int32_t* __restrict__ blk_start, const int32_t* __restrict__ blk_len,
+                                                           const int32_t* __restrict__ blk_t32, const int4* __restrict__ ranges,
+                                                           int32_t* __restrict__ qbounds) {
+  const int b = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.x * 4 + wave;
+  const int len = blk_len[b];
+  if (32 * t >= len) return;
+  const int row = 32 * t + (lane & 31);
+  RangeBounds rb;
+  rb.init();
+  if (row < len) rb.add(ranges[blk_start[b] + row]);
+  rb.wave_reduce();
+  if (lane == 0) {
+    int32_t* o = qbounds + (int64_t)(blk_t32[b] + t) * 8;
+    o[0] = rb.lo_min[0]; o[1] = rb.lo_max[0]; o[2] = rb.hi_min[0]; o[3] = rb.hi_max[0];
+    o[4] = rb.lo_min[1]; o[5] = rb.lo_max[1]; o[6] = rb.hi_min[1]; o[7] = rb.hi_max[1];
+  }
+}
 
 // Walks (table row, query head of the group, 64-query tile) for one KV tile.
+template <bool RANGES>
 struct QIter {
-  const int32_t *ent_start, *ent_len, *ent_kind, *ent_moff;
+  const int4* rec;       // per table row: {first query, length, mask kind, memory offset of the Q block}, {first 32-row tile, ..}
+  const int4* qbounds;   // range-bound summaries per 32-row tile, or null
   int e, e_end, hh, G, jt, n_t, jt0;
   int q0, q1, kind;
   int moff;  // the Q block's rows sit at (packed index + moff) in the Q-type buffers
+  int t32;   // index of the Q block's first 32-row tile in qbounds
   int qs;    // first query of the current tile
-  __device__ QIter(const DevGroup& g, int unit, int G_) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind), ent_moff(g.ent_moff) {
-    e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; moff = 0; qs = 0;
+  __device__ QIter(const DevGroup& g, int unit, int G_, const int32_t* qb)
+      : rec((const int4*)g.ent_rec), qbounds((const int4*)qb) {
+    e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; moff = 0; t32 = 0; qs = 0;
   }
-  // k_lo: first key of the workgroup's tile.  Under CAUSAL, query tiles that end before k_lo see nothing.
-  __device__ bool next(int k_lo) {
+  // Which of the (at most 64) 64-query tiles of the current RANGES row may see a key of [k_lo, k_end): lane l merges
+  // the bounds of the two 32-row halves of tile l.  Returns the ballot (wave-uniform).
+  __device__ unsigned long long tiles_that_see(int k_lo, int k_end) const {
+    const int tile = threadIdx.x & 63;
+    bool see = false;
+    if (tile < n_t) {
+      const int n32 = (q1 - q0 + 31) >> 5;
+      const int4* p = qbounds + (int64_t)(t32 + 2 * tile) * 2;
+      int4 a = p[0], b = p[1];
+      if (2 * tile + 1 < n32) {
+        const int4 c = p[2], d = p[3];
+        a.x = min(a.x, c.x); a.w = max(a.w, c.w); b.x = min(b.x, d.x); b.w = max(b.w, d.w);
+      }
+      see = (k_lo < a.w && k_end > a.x) || (k_lo < b.w && k_end > b.x);   // x = smallest start, w = largest end
+    }
+    return __ballot(see);
+  }
+  // [k_lo, k_end): the keys of the workgroup's tile.  Under CAUSAL, query tiles that end before k_lo see nothing;
+  // under RANGES, the walk is narrowed to the span between the first and the last tile whose rows' ranges reach the
+  // keys (tiles inside the span that see nothing are left to the per-sub-tile test).
+  __device__ bool next(int k_lo, int k_end) {
     for (;;) {
       jt++;
       if (jt >= n_t) {
@@ -203,9 +250,15 @@ struct QIter {
           e++;
           if (e >= e_end) return false;
           hh = 0;
-          q0 = uni(ent_start[e]); q1 = q0 + uni(ent_len[e]); kind = uni(ent_kind[e]); moff = uni(ent_moff[e]);
+          const int4 r = rec[2 * e];
+          q0 = uni(r.x); q1 = q0 + uni(r.y); kind = uni(r.z); moff = uni(r.w); t32 = uni(rec[2 * e + 1].x);
           n_t = (q1 - q0 + kTN - 1) / kTN;
           jt0 = kind == 1 ? max(0, (k_lo - q0) / kTN) : 0;
+          if (RANGES && kind == 2 && qbounds && n_t <= 64) {
+            const unsigned long long m = tiles_that_see(k_lo, k_end);
+            if (m == 0) { n_t = 0; }
+            else { jt0 = __builtin_ctzll(m); n_t = 64 - __builtin_clzll(m); }
+          }
         }
         jt = jt0 - 1;
         continue;
@@ -224,6 +277,7 @@ struct DkvState {
   TileDma dmaq, dmao;
 };
 
+template <bool RANGES>
 __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int qt, int qs32, int q1, int kind,
                                             int k_end, float c_log2, int lane, bool MASK) {
   const int lh = lane >> 5;
@@ -278,7 +332,7 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
     // clamped duplicates of its last row and must not count
     const int qb0 = qs32 + 4 * lh;
     const bool kok = st.kj < k_end;
-    if (kind == 2) {
+    if (RANGES && kind == 2) {
       const int4* rg_lds = (const int4*)(stage + kStageRanges) + 32 * qt + 4 * lh;
 #pragma unroll
       for (int r = 0; r < 16; r++) {
@@ -319,6 +373,8 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
   }
 }
 
+// RANGES = false: the table has no RANGES row; everything that serves them is compiled out.
+template <bool RANGES>
 __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t) {
   constexpr int TK = 128;
   __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];
@@ -363,7 +419,7 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   }
   const float c_log2 = t.scale * kLog2e;
 
-  QIter it(g, w.unit, G);
+  QIter<RANGES> it(g, w.unit, G, t.qbounds);
   auto issue = [&](char* stage) {
     const int head = hk * G + it.hh;
     const int last = it.q1 - 1;
@@ -373,15 +429,18 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
     const int qmem = qrow + it.moff;
     if (wave == 0) dma4((unsigned)qmem * 4u, uni_ptr(t.lse2 + (int64_t)head * t.q_rows), lds_addr(stage + kStageLse));
     if (wave == 1) dma4((unsigned)qmem * 4u, uni_ptr(t.delta + (int64_t)head * t.q_rows), lds_addr(stage + kStageDelta));
-    if (wave == 2 && it.kind == 2) dma16((unsigned)qrow * 16u, uni_ptr(t.ranges), lds_addr(stage + kStageRanges));
+    if (RANGES && wave == 2 && it.kind == 2) dma16((unsigned)qrow * 16u, uni_ptr(t.ranges), lds_addr(stage + kStageRanges));
+    // the bounds of the tile's two halves (4 x 16 B; the other lanes repeat them into the reserved space)
+    if (RANGES && wave == 3 && it.kind == 2 && t.qbounds)
+      dma16((unsigned)(lane & 3) * 16u, uni_ptr(t.qbounds + (int64_t)(it.t32 + 2 * it.jt) * 8), lds_addr(stage + kStageBounds));
   };
-  bool have = it.next(k_lo);
+  bool have = it.next(k_lo, k_end);
   if (have) issue(stage0);
   DCP_WAIT_VMCNT(0);
   __syncthreads();
   auto step = [&](const char* cur, char* nxt) {
     const int qs = it.qs, q1 = it.q1, kind = it.kind;
-    have = it.next(k_lo);
+    have = it.next(k_lo, k_end);
     if (have) issue(nxt);
     if (w_rows > 0) {
 #pragma unroll
@@ -392,7 +451,19 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
         int cls = kPartial;
         if (kind == 0) cls = whole ? kFull : kPartial;
         if (kind == 1) cls = min(qs32 + 31, q1 - 1) < wk_lo ? kSkip : ((whole && qs32 >= wk_hi) ? kFull : kPartial);
-        if (cls != kSkip) dkv_subtile(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane, cls == kPartial);
+        if (RANGES && kind == 2 && t.qbounds) {
+          // the 32 queries' range bounds against the wave's keys (the empty asm keeps the compiler from hoisting
+          // these LDS reads, and their wait, out of the branch into every step)
+          asm volatile("" ::: "memory");
+          const int4* bp = (const int4*)(cur + kStageBounds) + 2 * qt;
+          const int4 a = bp[0], b = bp[1];
+          RangeBounds qb;
+          qb.lo_min[0] = uni(a.x); qb.lo_max[0] = uni(a.y); qb.hi_min[0] = uni(a.z); qb.hi_max[0] = uni(a.w);
+          qb.lo_min[1] = uni(b.x); qb.lo_max[1] = uni(b.y); qb.hi_min[1] = uni(b.z); qb.hi_max[1] = uni(b.w);
+          if (!qb.may_see(wk_lo, wk_hi + 1)) cls = kSkip;
+          else if (whole && qb.all_see(wk_lo, wk_hi + 1)) cls = kFull;
+        }
+        if (cls != kSkip) dkv_subtile<RANGES>(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane, cls == kPartial);
       }
     }
     DCP_WAIT_VMCNT(0);
@@ -420,6 +491,15 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
     }
 }
 
+dcp_status_t mfma_range_bounds(const int32_t* blk_start, const int32_t* blk_len, const int32_t* blk_t32, int32_t n_blocks,
+                               int32_t block_size, const int32_t* ranges, int32_t* qbounds, hipStream_t s) {
+  if (n_blocks == 0) return DCP_OK;
+  hipLaunchKernelGGL(range_bounds_kernel, dim3((block_size + 127) / 128, n_blocks), dim3(256), 0, s, blk_start, blk_len, blk_t32,
+                     (const int4*)ranges, qbounds);
+  DCP_HIP_TRY(hipGetLastError());
+  return DCP_OK;
+}
+
 int mfma_dq_tile() { return 128; }
 int mfma_dkv_tile() { return 128; }
 
@@ -434,7 +514,8 @@ dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s) {
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
   const int per_xcd = (g.n_items * t.hkv + 7) / 8;
-  hipLaunchKernelGGL(mfma_dkv_kernel, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  if (t.ranges) hipLaunchKernelGGL(mfma_dkv_kernel<true>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  else hipLaunchKernelGGL(mfma_dkv_kernel<false>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;
 }

@@ -267,13 +267,12 @@ __device__ __forceinline__ float xhalf_sum(float x) {
 // Walks the (table row, key tile) pairs of a unit that the workgroup cannot skip.  All state is
 // wave-uniform.
 struct KvIter {
-  const int32_t *ent_start, *ent_len, *ent_kind;
+  const int4* rec;   // per table row: {first key, length, mask kind, memory offset of the KV block}, {..}
   int e, e_end, jt, n_t;
-  const int32_t* ent_moff;
   int c0, c1, kind;
   int moff;  // the KV block's rows sit at (packed index + moff) in the KV-type buffers
   int ks;    // first key of the current tile
-  __device__ KvIter(const DevGroup& g, int unit) : ent_start(g.ent_start), ent_len(g.ent_len), ent_kind(g.ent_kind), ent_moff(g.ent_moff) {
+  __device__ KvIter(const DevGroup& g, int unit) : rec((const int4*)g.ent_rec) {
     e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); jt = 0; n_t = 0; c0 = c1 = kind = 0; moff = 0; ks = 0;
   }
   // Advances to the next tile some row of [.., q_hi] may see; false when the unit is done.
@@ -283,7 +282,8 @@ struct KvIter {
       if (jt >= n_t) {
         e++;
         if (e >= e_end) return false;
-        c0 = uni(ent_start[e]); c1 = c0 + uni(ent_len[e]); kind = uni(ent_kind[e]); moff = uni(ent_moff[e]);
+        const int4 r = rec[2 * e];
+        c0 = uni(r.x); c1 = c0 + uni(r.y); kind = uni(r.z); moff = uni(r.w);
         n_t = (c1 - c0 + kTN - 1) / kTN;
         if (kind == 1) n_t = min(n_t, max(0, (q_hi - c0) / kTN + 1));  // tiles starting after q_hi are empty
         jt = -1;

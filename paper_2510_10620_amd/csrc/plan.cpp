@@ -171,6 +171,8 @@ extern "C" dcp_status_t dcp_plan_create(dcp_plan_t** out, const int32_t* cu, int
   pl->total_tokens = n_seq > 0 ? cu[n_seq] : 0;
   pl->q_rows = pl->kv_rows = pl->total_tokens;
   pl->q_moff.assign(pl->n_blocks, 0);
+  pl->blk_t32.assign(pl->n_blocks + 1, 0);
+  for (int32_t b = 0; b < pl->n_blocks; b++) pl->blk_t32[b + 1] = pl->blk_t32[b] + (p.len[b] + 31) / 32;
   pl->kv_moff.assign(pl->n_blocks, 0);
   pl->cu.assign(cu, cu + (n_seq > 0 ? n_seq + 1 : 0));
   pl->blk_start = p.start;
@@ -346,7 +348,7 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     return off;
   };
   size_t o_bs = put(blk_start), o_bl = put(blk_len);
-  struct Off { size_t ub, uo, ptr, es, el, ek, um, em; } go[3];
+  struct Off { size_t ub, uo, ptr, es, el, ek, um, em, et, er; } go[3];
   HostGroup* gs[3] = {&fwd, &bwdq, &bwdkv};
   for (int i = 0; i < 3; i++) {
     // memory offsets: own side = Q for the query-side groups, KV for the dK/dV group
@@ -355,15 +357,25 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     std::vector<int32_t> um(gs[i]->unit_blk.size(), 0), em(gs[i]->ent_blk.size(), 0);
     for (size_t u = 0; u < um.size(); u++)
       if (gs[i]->unit_blk[u] >= 0) um[u] = own[gs[i]->unit_blk[u]];
-    for (size_t e = 0; e < em.size(); e++) em[e] = other[gs[i]->ent_blk[e]];
+    std::vector<int32_t> et(gs[i]->ent_blk.size(), 0);
+    for (size_t e = 0; e < em.size(); e++) { em[e] = other[gs[i]->ent_blk[e]]; et[e] = blk_t32[gs[i]->ent_blk[e]]; }
     go[i] = {put(gs[i]->unit_blk), put(gs[i]->unit_out), put(gs[i]->ptr), put(gs[i]->ent_start), put(gs[i]->ent_len), put(gs[i]->ent_kind),
-             put(um), put(em)};
+             put(um), put(em), put(et), 0};
+    {
+      std::vector<int32_t> rec(gs[i]->ent_blk.size() * 8, 0);
+      for (size_t e = 0; e < em.size(); e++) {
+        rec[8 * e] = gs[i]->ent_start[e]; rec[8 * e + 1] = gs[i]->ent_len[e]; rec[8 * e + 2] = gs[i]->ent_kind[e];
+        rec[8 * e + 3] = em[e]; rec[8 * e + 4] = et[e];
+      }
+      while (host.size() % 8) host.push_back(0);   // records are read as 16-byte vectors
+      go[i].er = put(rec);
+    }
   }
   size_t o_mp = put(merge_ptr), o_mi = put(merge_idx), o_sq = put(slot_qblk);
   // first row of every block in the Q-type buffers (-1: absent), for the merge
   std::vector<int32_t> q_mem0(n_blocks);
   for (int32_t b = 0; b < n_blocks; b++) q_mem0[b] = (buffers && q_slot[b] < 0) ? -1 : blk_start[b] + q_moff[b];
-  size_t o_qm = put(q_mem0);
+  size_t o_qm = put(q_mem0), o_t32 = put(blk_t32);
   host.push_back(0);
   DCP_HIP_TRY(hipMalloc((void**)&dev_arena, host.size() * sizeof(int32_t)));
   hipError_t e = hipMemcpyAsync(dev_arena, host.data(), host.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream);
@@ -384,6 +396,8 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     ds[i]->ent_kind = dev_arena + go[i].ek;
     ds[i]->unit_moff = dev_arena + go[i].um;
     ds[i]->ent_moff = dev_arena + go[i].em;
+    ds[i]->ent_t32 = dev_arena + go[i].et;
+    ds[i]->ent_rec = dev_arena + go[i].er;
     ds[i]->blk_start = dev_arena + o_bs;
     ds[i]->blk_len = dev_arena + o_bl;
     ds[i]->items = nullptr;
@@ -394,6 +408,7 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
   d_merge_idx = dev_arena + o_mi;
   d_slot_qblk = dev_arena + o_sq;
   d_q_mem0 = dev_arena + o_qm;
+  d_blk_t32 = dev_arena + o_t32;
   return DCP_OK;
 }
 

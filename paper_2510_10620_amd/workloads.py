@@ -163,7 +163,8 @@ class Workload:
 
 
 def make_workload(cfg: int, tokens: Optional[int] = None) -> Workload:
-    """The five benchmark configurations.  `tokens` shrinks the packed batch (same
+    """The five benchmark configurations, plus the two remaining mask families of the paper (6, 7) at the
+    shapes of configs 3 / 4.  `tokens` shrinks the packed batch (same
     distribution, same seeds) for parity cases the CPU oracle can finish."""
     if cfg == 1:
         w = Workload("tiny_causal_f32", cu_from_lengths([128, 384]), 64, 1, 1, 64, "f32",
@@ -187,8 +188,21 @@ def make_workload(cfg: int, tokens: Optional[int] = None) -> Workload:
         lens = draw_lengths(T, "lognormal", 1024, 131072, seed=5, median=8192)
         w = Workload("dcp_share_bf16", cu_from_lengths(lens), 2048, 32, 8, 128, "bf16",
                      MaskSpec("causal"), 105, 1.0 / math.sqrt(128), share=(8, 205, 4, 305))
+    elif cfg == 6:
+        # Sec. 7.1 "Attention Masks", causal blockwise: 256-token mask blocks, a window of 2 blocks, one sink
+        # block, the final (test) block attends to everything before it
+        T = tokens or 131072
+        lens = draw_lengths(T, "uniform", 8192, 65536, seed=6)
+        w = Workload("causal_blockwise_bf16", cu_from_lengths(lens), 1024, 32, 8, 128, "bf16",
+                     MaskSpec("causal_blockwise", window=2, sink=1, mblock=256), 106, 1.0 / math.sqrt(128))
+    elif cfg == 7:
+        # Sec. 7.1 "Attention Masks", shared question: one question and 4 answers of 20 % of the sequence each
+        T = tokens or 131072
+        lens = draw_lengths(T, "lognormal", 1024, 65536, seed=7, median=8192)
+        w = Workload("shared_question_bf16", cu_from_lengths(lens), 1024, 32, 8, 128, "bf16",
+                     MaskSpec("shared_question", n_answers=4, frac=0.2), 107, 1.0 / math.sqrt(128))
     else:
-        raise ValueError(f"config {cfg} not in 1..5")
+        raise ValueError(f"config {cfg} not in 1..7")
     w.softmax_scale = 1.0 / math.sqrt(w.d)
     w.ranges = attn_ranges(w.mask, w.cu_seqlens)
     return w
