@@ -55,7 +55,9 @@ __device__ __forceinline__ void dq_subtile(DqState& st, const char* k_lds, const
   }
 }
 
+template <bool RANGES>
 __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t) {
+  if (!RANGES) t.ranges = nullptr;
   constexpr int TM = 128;
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   const bf16_t* vbase = (const bf16_t*)t.v + (int64_t)hk * t.v_sh;
 
   KvIter it(g, w.unit);
-  bool have = it.next(q_hi, rb);
+  bool have = it.next<RANGES>(q_hi, rb);
   if (have) {
     st.dmak.load(stage0, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
     st.dmav.load(stage0 + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
@@ -142,8 +144,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   DCP_WAIT_VMCNT(0);
   __syncthreads();
   auto step = [&](const char* cur, char* nxt) {
-    const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
-    have = it.next(q_hi, rb);
+    const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = RANGES ? it.kind : (it.kind & 1);
+    have = it.next<RANGES>(q_hi, rb);
     if (have) {
       st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
       st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
@@ -506,7 +508,8 @@ int mfma_dkv_tile() { return 128; }
 dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
   const int per_xcd = (g.n_items * t.hq + 7) / 8;
-  hipLaunchKernelGGL(mfma_dq_kernel, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  if (t.ranges) hipLaunchKernelGGL(mfma_dq_kernel<true>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  else hipLaunchKernelGGL(mfma_dq_kernel<false>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;
 }

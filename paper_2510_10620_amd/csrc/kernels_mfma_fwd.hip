@@ -178,8 +178,10 @@ __device__ __forceinline__ void fwd_tile64(FwdState<NQ>& st, const char* k_lds, 
       }
 }
 
-template <int NQ>
+// RANGES = false: the table has no RANGES row; t.ranges is null and every use of it folds away.
+template <int NQ, bool RANGES>
 __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGroup g, KTensors t) {
+  if (!RANGES) t.ranges = nullptr;
   constexpr int WR = FwdCfg<NQ>::kWaveRows, TM = FwdCfg<NQ>::kTileM;
   // two stages, each [K tile | V tile]
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
   const bf16_t* vbase = (const bf16_t*)t.v + (int64_t)hk * t.v_sh;
 
   KvIter it(g, w.unit);
-  bool have = it.next(q_hi, rb);
+  bool have = it.next<RANGES>(q_hi, rb);
   if (have) {
     st.dmak.load(stage0, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
     st.dmav.load(stage0 + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
@@ -271,8 +273,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
 
   // one pipeline step: prefetch the next tile into `nxt`, compute the current one from `cur`
   auto step = [&](const char* cur, char* nxt) {
-    const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = it.kind;
-    have = it.next(q_hi, rb);
+    const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = RANGES ? it.kind : (it.kind & 1);
+    have = it.next<RANGES>(q_hi, rb);
     if (have) {
       st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
       st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
@@ -335,7 +337,8 @@ dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
   const int total = g.n_items * t.hq;
   const int per_xcd = (total + 7) / 8;
-  hipLaunchKernelGGL(mfma_fwd_kernel<DCP_FWD_NQ>, dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
+  if (t.ranges) hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, true>), dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, false>), dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;
 }

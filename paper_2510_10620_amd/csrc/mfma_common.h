@@ -276,6 +276,8 @@ struct KvIter {
     e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); jt = 0; n_t = 0; c0 = c1 = kind = 0; moff = 0; ks = 0;
   }
   // Advances to the next tile some row of [.., q_hi] may see; false when the unit is done.
+  // RANGES = false: the table has no RANGES row (nothing of the range machinery is compiled in).
+  template <bool RANGES>
   __device__ bool next(int q_hi, const RangeBounds& rb) {
     for (;;) {
       jt++;
@@ -290,7 +292,7 @@ struct KvIter {
         continue;
       }
       ks = c0 + jt * kTN;
-      if (kind != 2 || rb.may_see(ks, min(ks + kTN, c1))) return true;
+      if (!RANGES || kind != 2 || rb.may_see(ks, min(ks + kTN, c1))) return true;
     }
   }
 };
