@@ -141,32 +141,36 @@ __device__ __forceinline__ unsigned lds_addr(const void* p) { return (unsigned)(
 
 template <int PW>
 struct TileDmaT {
-  int row[PW];        // tile row this lane fetches in instruction u
-  int chunk[PW];      // byte offset of its 16-byte chunk inside the row
-  unsigned off[PW];   // row * stride + chunk, bytes
+  unsigned off[PW];   // row * stride + chunk of the 16 bytes this lane fetches in instruction u
   int sb;             // row stride, bytes
+  // instruction u of wave `wave` fills tile rows 4 (wave PW + u) .. + 3: lane >> 4 picks the row, lane & 15 the
+  // physical 16-byte chunk, which receives the logical chunk (lane & 15) ^ swz(row)
+  static __device__ __forceinline__ int row_of(int wave, int lane, int u) { return 4 * (wave * PW + u) + (lane >> 4); }
+  static __device__ __forceinline__ int chunk_of(int lane, int row) { return ((lane & 15) ^ swz(row)) * 16; }
   __device__ __forceinline__ void init(int wave, int lane, int64_t stride_t) {
     sb = (int)stride_t * 2;
 #pragma unroll
     for (int u = 0; u < PW; u++) {
-      row[u] = 4 * (wave * PW + u) + (lane >> 4);
-      chunk[u] = ((lane & 15) ^ swz(row[u])) * 16;
-      off[u] = (unsigned)(row[u] * sb + chunk[u]);
+      const int row = row_of(wave, lane, u);
+      off[u] = (unsigned)(row * sb + chunk_of(lane, row));
     }
   }
   __device__ __forceinline__ void load(char* tile, const bf16_t* base, int row_start, int row_last, int wave) const {
     // wave-uniform by construction; readfirstlane makes it provably so (it must live in SGPRs)
-    const uint64_t bv = (uint64_t)((const char*)base + (int64_t)row_start * sb);
-    const void* b = (const void*)(((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(bv >> 32)) << 32) |
-                                  (unsigned)__builtin_amdgcn_readfirstlane((int)bv));
+    const void* b = uni_ptr((const char*)base + (int64_t)row_start * sb);
     const unsigned l0 = lds_addr(tile) + wave * PW * 1024;
     if (row_start + kTN - 1 <= row_last) {
 #pragma unroll
       for (int u = 0; u < PW; u++) dma16(off[u], b, l0 + u * 1024);
     } else {
-      const int lim = row_last - row_start;
+      // ragged end: rows past row_last repeat it (recomputed here: this path is rare and the lane's
+      // row / chunk numbers are not worth registers)
+      const int lim = row_last - row_start, lane = threadIdx.x & 63;
 #pragma unroll
-      for (int u = 0; u < PW; u++) dma16((unsigned)(min(row[u], lim) * sb + chunk[u]), b, l0 + u * 1024);
+      for (int u = 0; u < PW; u++) {
+        const int row = row_of(wave, lane, u);
+        dma16((unsigned)(min(row, lim) * sb + chunk_of(lane, row)), b, l0 + u * 1024);
+      }
     }
   }
 };
