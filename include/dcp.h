@@ -221,6 +221,27 @@ dcp_status_t dcp_copy_list_destroy(dcp_copy_list_t* list);
 dcp_status_t dcp_blockwise_copy(dcp_copy_list_t* list, const void* src, int64_t src_row_stride,
                                 void* dst, int64_t dst_row_stride, int64_t row_bytes, void* stream);
 
+/* Communication volume of a placement (host only; Sec. 4.1, the volume of a configuration, and Sec. 4.2, the
+ * connectivity metric of the hypergraph whose hyperedges join each data block to the computation blocks that
+ * consume it or contribute to it).  A table row is one computation block (all heads): it consumes Q block q_blk
+ * and KV block kv_blk and contributes to O block q_blk; SKIP rows are not computation blocks.
+ *   blk_dev   host int32 [n_blocks]: device of each block's tokens (their Q, KV and O live together, Sec. 4.1)
+ *   comp_dev  host int32 [n_entries]: device of each computation block
+ *   *_bytes_per_token: bytes one token holds in Q, in K and V together, in O (all heads)
+ * Outputs (each may be NULL):
+ *   pairwise      sum over computation blocks of Size(input)[Dev(input) != Dev(C)] + Size(output)[Dev(output) != Dev(C)]
+ *   connectivity  sum over hyperedges of s_e (lambda_e - 1): every remote device moves the block once
+ *   n_hyperedges  hyperedges with at least one computation block
+ *   send, recv    host int64 [n_devices]: bytes each device sends / receives under the connectivity model (an input
+ *                 block goes from its owner to each other device that computes with it; a partial output goes from
+ *                 each other device that contributes to the block's owner)
+ * DCP_ERR_BAD_TABLE: block or device id out of range. */
+dcp_status_t dcp_comm_volume(const int32_t* cu_seqlens_host, int32_t n_seq, int32_t block_size,
+                             const int32_t* table_host, int64_t n_entries, const int32_t* blk_dev,
+                             const int32_t* comp_dev, int32_t n_devices, int64_t q_bytes_per_token,
+                             int64_t kv_bytes_per_token, int64_t o_bytes_per_token, int64_t* pairwise,
+                             int64_t* connectivity, int64_t* n_hyperedges, int64_t* send, int64_t* recv);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
  * bracketed by hipEvents recorded on the launch stream (the kernels of one backward call are timed
  * one by one).  dcp_profile_read synchronises on the recorded events, returns the summed duration

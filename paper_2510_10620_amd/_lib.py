@@ -32,6 +32,8 @@ class Tensors(ctypes.Structure):
 _SIGS = {
     "dcp_build_block_table": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, i32p, ctypes.c_int64, i64p]),
     "dcp_count_pairs": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, i64p]),
+    "dcp_comm_volume": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int32,
+                                       ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, i64p, i64p, i64p, i64p, i64p]),
     "dcp_plan_create": (ctypes.c_int, [ctypes.POINTER(vp), i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, ctypes.c_int32]),
     "dcp_plan_set_block_buffers": (ctypes.c_int, [vp, i32p, ctypes.c_int32, i32p, ctypes.c_int32]),
     "dcp_plan_destroy": (ctypes.c_int, [vp]),

@@ -66,6 +66,22 @@ def dcp_count_pairs(cu_seqlens, block_size, table, attn_ranges=None):
     return out
 
 
+def dcp_comm_volume(cu_seqlens, block_size, table, blk_dev, comp_dev, n_devices, q_bytes, kv_bytes, o_bytes):
+    """-> dict(pairwise, connectivity, hyperedges, send[n_devices], recv[n_devices]); host only."""
+    lib = _lib.load()
+    cu, cu_p = _i32(cu_seqlens)
+    tb = np.ascontiguousarray(np.asarray(table, dtype=np.int32).reshape(-1, 3))
+    bd, bd_p = _i32(blk_dev)
+    cd, cd_p = _i32(comp_dev)
+    pw, cn, ne = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    send = np.zeros(n_devices, dtype=np.int64)
+    recv = np.zeros(n_devices, dtype=np.int64)
+    _check(lib.dcp_comm_volume(cu_p, len(cu) - 1, block_size, tb.ctypes.data_as(_lib.i32p), len(tb), bd_p, cd_p, n_devices,
+                               q_bytes, kv_bytes, o_bytes, ctypes.byref(pw), ctypes.byref(cn), ctypes.byref(ne),
+                               send.ctypes.data_as(_lib.i64p), recv.ctypes.data_as(_lib.i64p)))
+    return dict(pairwise=pw.value, connectivity=cn.value, hyperedges=ne.value, send=send.tolist(), recv=recv.tolist())
+
+
 class Plan:
     """Owner of a dcp_plan_t*."""
 

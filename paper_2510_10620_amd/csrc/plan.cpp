@@ -124,6 +124,59 @@ extern "C" dcp_status_t dcp_count_pairs(const int32_t* cu, int32_t n_seq, int32_
   return DCP_OK;
 }
 
+extern "C" dcp_status_t dcp_comm_volume(const int32_t* cu, int32_t n_seq, int32_t B, const int32_t* table, int64_t n_entries,
+                                        const int32_t* blk_dev, const int32_t* comp_dev, int32_t n_devices, int64_t q_bytes,
+                                        int64_t kv_bytes, int64_t o_bytes, int64_t* pairwise, int64_t* connectivity,
+                                        int64_t* n_hyperedges, int64_t* send, int64_t* recv) {
+  Partition p;
+  dcp_status_t st = make_partition(cu, n_seq, B, &p);
+  if (st != DCP_OK) return st;
+  const int32_t nb = (int32_t)p.start.size();
+  if (n_entries < 0 || (n_entries > 0 && (!table || !comp_dev))) return fail(DCP_ERR_INVALID_ARG, "table / comp_dev is NULL or n_entries < 0");
+  if (nb > 0 && !blk_dev) return fail(DCP_ERR_INVALID_ARG, "blk_dev is NULL");
+  if (n_devices <= 0) return fail(DCP_ERR_INVALID_ARG, "n_devices must be positive");
+  if (q_bytes < 0 || kv_bytes < 0 || o_bytes < 0) return fail(DCP_ERR_INVALID_ARG, "negative bytes per token");
+  for (int32_t b = 0; b < nb; b++)
+    if (blk_dev[b] < 0 || blk_dev[b] >= n_devices) return fail(DCP_ERR_BAD_TABLE, "blk_dev[" + std::to_string(b) + "] out of range");
+  // per data block: the set of devices that compute with it (one bit set per device, kept as sorted vectors)
+  std::vector<std::vector<int32_t>> q_users(nb), kv_users(nb);
+  int64_t pw = 0;
+  for (int64_t e = 0; e < n_entries; e++) {
+    const int32_t qb = table[3 * e], kb = table[3 * e + 1], kind = table[3 * e + 2], d = comp_dev[e];
+    if (kind < 0 || kind > 3) return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": bad mask_kind");
+    if (qb < 0 || qb >= nb || kb < 0 || kb >= nb) return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": block id out of range");
+    if (kind == DCP_MASK_SKIP) continue;
+    if (d < 0 || d >= n_devices) return fail(DCP_ERR_BAD_TABLE, "comp_dev[" + std::to_string(e) + "] out of range");
+    if (blk_dev[qb] != d) pw += (int64_t)p.len[qb] * (q_bytes + o_bytes);
+    if (blk_dev[kb] != d) pw += (int64_t)p.len[kb] * kv_bytes;
+    q_users[qb].push_back(d);
+    kv_users[kb].push_back(d);
+  }
+  int64_t conn = 0, edges = 0;
+  if (send) std::fill(send, send + n_devices, 0);
+  if (recv) std::fill(recv, recv + n_devices, 0);
+  for (int32_t b = 0; b < nb; b++) {
+    const int32_t owner = blk_dev[b];
+    for (int side = 0; side < 3; side++) {          // 0: Q block, 1: KV block, 2: O block (made by the users of the Q block)
+      std::vector<int32_t>& u = side == 1 ? kv_users[b] : q_users[b];
+      if (u.empty()) continue;
+      if (side != 2) { std::sort(u.begin(), u.end()); u.erase(std::unique(u.begin(), u.end()), u.end()); }
+      edges++;
+      const int64_t size = (int64_t)p.len[b] * (side == 0 ? q_bytes : (side == 1 ? kv_bytes : o_bytes));
+      for (int32_t d : u) {
+        if (d == owner) continue;
+        conn += size;
+        if (side != 2) { if (send) send[owner] += size; if (recv) recv[d] += size; }
+        else { if (send) send[d] += size; if (recv) recv[owner] += size; }
+      }
+    }
+  }
+  if (pairwise) *pairwise = pw;
+  if (connectivity) *connectivity = conn;
+  if (n_hyperedges) *n_hyperedges = edges;
+  return DCP_OK;
+}
+
 // Groups kept rows by unit_of(row); inside a unit ascending by other(row), stable.
 template <class UnitOf, class OtherOf>
 static void build_group(const dcp_plan& pl, const std::vector<int64_t>& kept, int32_t n_units, UnitOf unit_of,

@@ -201,3 +201,42 @@ def test_block_buffer_slot_validation():
     pl = P.dcp_plan_create(cu, 32, sub)
     s5 = ok.copy(); s5[5] = -1
     P.dcp_plan_set_block_buffers(pl, s5, 6, s5, 6)
+
+
+# ------------------------------------------------------------------ communication volume (host side)
+@pytest.mark.parametrize("spec", SPECS, ids=lambda s: s.kind)
+def test_comm_volume_matches_oracle(spec):
+    from oracle import placement as OP
+    rng = np.random.default_rng(13)
+    cu = W.cu_from_lengths([150, 37, 260])
+    B = 24
+    table = _oracle_table(spec, cu, B)
+    skip = np.array([[0, 0, 3]], dtype=np.int32)            # a SKIP row is no computation block
+    table = np.concatenate([table, skip])
+    part = OB.block_partition(cu, B)
+    blk_len = part["blk_end"] - part["blk_start"]
+    for R in (1, 3, 8):
+        blk_dev = rng.integers(0, R, len(blk_len)).astype(np.int32)
+        comp_dev = rng.integers(0, R, len(table)).astype(np.int32)
+        got = P.dcp_comm_volume(cu, B, table, blk_dev, comp_dev, R, 8192, 4096, 8320)
+        ref = OP.comm_volume(blk_len, table, blk_dev, comp_dev, R, 8192, 4096, 8320)
+        assert got == ref
+
+
+def test_comm_volume_errors():
+    cu = np.array([0, 64], dtype=np.int32)
+    table = np.array([[0, 0, 1], [1, 0, 0], [1, 1, 1]], dtype=np.int32)
+    ok = dict(blk_dev=np.array([0, 1], np.int32), comp_dev=np.array([0, 1, 1], np.int32))
+    P.dcp_comm_volume(cu, 32, table, ok["blk_dev"], ok["comp_dev"], 2, 1, 1, 1)
+    for kw, code in ((dict(blk_dev=np.array([0, 2], np.int32)), P.DCP_ERR_BAD_TABLE),
+                     (dict(comp_dev=np.array([0, 1, -1], np.int32)), P.DCP_ERR_BAD_TABLE)):
+        a = dict(ok); a.update(kw)
+        with pytest.raises(P.DcpError) as e:
+            P.dcp_comm_volume(cu, 32, table, a["blk_dev"], a["comp_dev"], 2, 1, 1, 1)
+        assert e.value.status == code
+    with pytest.raises(P.DcpError) as e:
+        P.dcp_comm_volume(cu, 32, np.array([[2, 0, 0]], np.int32), ok["blk_dev"], np.array([0], np.int32), 2, 1, 1, 1)
+    assert e.value.status == P.DCP_ERR_BAD_TABLE
+    with pytest.raises(P.DcpError) as e:
+        P.dcp_comm_volume(cu, 32, table, ok["blk_dev"], ok["comp_dev"], 0, 1, 1, 1)
+    assert e.value.status == P.DCP_ERR_INVALID_ARG

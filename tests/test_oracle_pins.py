@@ -476,3 +476,70 @@ def test_block_buffer_gather_scatter_and_copy_lists_agree():
     lb = BB.gather_rows_hT(l, bs, bl, slots, n_slots, B, fill=np.inf)
     assert np.array_equal(BB.scatter_rows_hT(lb, bs, bl, slots, B, T), l)
     assert lb[1, slots[b] * B + 2] == l[1, bs[b] + 2]
+
+
+# ------------------------------------------------------------------ communication volume of a placement
+def _sq_example():
+    """Sec. 4.1's example: one sequence of 6 tokens, block size 2, shared-question mask (a question and two answers)."""
+    from oracle import blocks as OB_, masks as OM_
+    cu = np.array([0, 6], dtype=np.int32)
+    spec = W.MaskSpec("shared_question", n_answers=2, frac=1.0 / 3.0)
+    table = OB_.table_from_mask(lambda s, L, r0, r1: OM_.dense_rows(spec, L, r0, r1), cu, 2)
+    return cu, table
+
+
+def test_comm_volume_paper_example_and_hand_cases():
+    from oracle import placement as OP
+    cu, table = _sq_example()
+    pairs = sorted((int(q), int(k)) for q, k, _ in table)
+    assert pairs == [(0, 0), (1, 0), (1, 1), (2, 0), (2, 2)]          # the second answer does not see the first
+    blk_len = [2, 2, 2]
+    # Sec. 4.2: "Nine hyperedges are built in total" (3 Q + 3 KV + 3 O data blocks)
+    r = OP.comm_volume(blk_len, table, [0, 0, 0], [0] * 5, 2, 10, 6, 10)
+    assert r["hyperedges"] == 9 and r["pairwise"] == 0 and r["connectivity"] == 0
+    # block 2 and its computation on device 1: it fetches KV block 0 once (its own K/V is local)
+    r = OP.comm_volume(blk_len, table, [0, 0, 1], [0, 0, 0, 1, 1], 2, 10, 6, 10)
+    assert r["pairwise"] == 2 * 6 and r["connectivity"] == 2 * 6 and r["send"] == [12, 0] and r["recv"] == [0, 12]
+    # the same tokens, but both computation blocks of Q block 2 run on device 0: Q_2 and KV_2 go to device 0
+    # (Q once per hyperedge, twice per computation block) and two partial outputs come back (once per hyperedge)
+    r = OP.comm_volume(blk_len, table, [0, 0, 1], [0] * 5, 2, 10, 6, 10)
+    assert r["pairwise"] == 2 * (2 * 10 + 2 * 10) + 2 * 6
+    assert r["connectivity"] == 2 * 10 + 2 * 6 + 2 * 10
+    assert r["send"] == [20, 32] and r["recv"] == [32, 20]
+
+
+def test_comm_volume_invariants_on_random_placements():
+    """connectivity <= pairwise (a device that needs a block for several computation blocks moves it once), equality
+    when no (block, remote device) pair repeats; sends and receives balance; one device or data-parallel placement
+    (each sequence and its computation on one device) moves nothing."""
+    from oracle import placement as OP, blocks as OB_
+    rng = np.random.default_rng(12)
+    cu = np.array([0, 70, 100, 230], dtype=np.int32)
+    table = OB_.dense_causal_table(cu, 16)
+    table = table[table[:, 0] >= table[:, 1]]
+    part = OB_.block_partition(cu, 16)
+    blk_len = part["blk_end"] - part["blk_start"]
+    nb = len(blk_len)
+    for R in (1, 2, 5):
+        blk_dev = rng.integers(0, R, nb)
+        comp_dev = rng.integers(0, R, len(table))
+        r = OP.comm_volume(blk_len, table, blk_dev, comp_dev, R, 8, 4, 8)
+        assert r["connectivity"] <= r["pairwise"]
+        assert sum(r["send"]) == sum(r["recv"]) == r["connectivity"]
+        assert r["hyperedges"] == 3 * nb
+        if R == 1:
+            assert r["pairwise"] == 0
+        # second opinion on the connectivity: distinct (block, remote device) pairs counted with numpy
+        tot = 0
+        for col, per_tok in ((0, 8), (1, 4), (0, 8)):
+            prs = np.unique(np.stack([table[:, col], comp_dev], axis=1), axis=0)
+            tot += sum(int(blk_len[b]) * per_tok for b, d in prs if blk_dev[b] != d)
+        assert tot == r["connectivity"]
+    dp = part["blk_seq"] % 2                                   # sequence s lives on device s % 2
+    r = OP.comm_volume(blk_len, table, dp, dp[table[:, 0]], 2, 8, 4, 8)
+    assert r["pairwise"] == 0 and r["connectivity"] == 0
+    # computation on the Q owner: only KV moves, each remote (kv, device) pair once per row -> pairwise == rows counted
+    owner = rng.integers(0, 3, nb)
+    r = OP.comm_volume(blk_len, table, owner, owner[table[:, 0]], 3, 8, 4, 8)
+    rows = sum(int(blk_len[k]) * 4 for q, k, _ in table if owner[q] != owner[k])
+    assert r["pairwise"] == rows
