@@ -186,6 +186,7 @@ def main():
         extra["share"] = share_section(torch, P, W, np, steps=max(3, args.steps // 4), warmup=2)
         extra["blockwise_copy"] = copy_section(torch, P, np, plan, q, steps=max(3, args.steps // 2))
         extra["other_masks"] = masks_section(torch, P, W, np, steps=3)
+        extra["execution_plan"] = executor_section(torch, P, W, np, steps=3)
 
     # one plain copy of known size (256 MiB read + 256 MiB written) through the library's sum
     # kernel with a single part: the reference dispatch that scales hardware byte counters
@@ -265,6 +266,67 @@ def share_section(torch, P, W, np, steps, warmup):
         res[name + "_ms"] = round(tot / max(n, 1), 4)
     res["merge_GBps"] = round(merge_bytes / (res["merge_ms"] * 1e-3) / 1e9, 1)
     res["merge_frac_hbm"] = round(res["merge_GBps"] / PEAK_HBM_GBPS, 3)
+    return res
+
+
+def executor_section(torch, P, W, np, steps):
+    """Config 5's share as an execution plan of 4 divisions (forward of each division into partial slots, merge,
+    backward).  The KV blocks a division uses first (beyond division 0's) arrive by a transfer: Comm.Launch hands a
+    Blockwise Copy to a second stream and Comm.Wait precedes the division's attention.  Timed against the same
+    instructions with the copies in line on the compute stream."""
+    w = W.make_workload(5)
+    table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+    n_shares, share_seed, n_div, div_seed = w.share
+    sub = table[W.deal_share(len(table), n_shares, share_seed, 0)]
+    slot, n_slots, _ = W.deal_divisions(sub[:, 0], n_div, div_seed)
+    perm = np.random.default_rng(div_seed).permutation(len(sub))
+    div = np.empty(len(sub), dtype=np.int64)
+    div[perm] = np.arange(len(sub)) % n_div
+    q, k, v, do = gen_tensors(torch, w, w.tensor_seed)
+    k_far, v_far = k.clone(), v.clone()
+    T, B = w.total_tokens, w.block_size
+    full = P.dcp_plan_create(w.cu_seqlens, B, sub, slot, n_slots)
+    plain = P.dcp_plan_create(w.cu_seqlens, B, sub)
+    blk_start, blk_len = full.export("BLK_START").astype(np.int64), full.export("BLK_LEN").astype(np.int64)
+    first = np.full(len(blk_start), n_div)
+    for d, kb in zip(div, sub[:, 1]):
+        first[kb] = min(first[kb], d)
+    o_part = torch.empty((n_slots, B, w.hq, w.d), dtype=torch.bfloat16, device="cuda")
+    lse_part = torch.empty((n_slots, w.hq, B), dtype=torch.float32, device="cuda")
+    out, lse = torch.empty_like(q), torch.empty((w.hq, T), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+    ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plain, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
+    lists, moved = {}, 0
+    for d in range(1, n_div):
+        need = np.nonzero(first == d)[0]
+        lists[d] = P.CopyList(np.stack([blk_start[need], blk_start[need], blk_len[need]], axis=1).astype(np.int32), T, T)
+        moved += 2 * int(blk_len[need].sum()) * k[0].numel() * k.element_size()
+    fwd = [P.instr_attn_fwd(P.dcp_plan_create(w.cu_seqlens, B, sub[div == d], slot[div == d], n_slots), q, k, v, o_part, lse_part,
+                            w.softmax_scale, rg) for d in range(n_div)]
+    tail = [P.instr_merge(full, o_part, lse_part, out, lse),
+            P.instr_attn_bwd(plain, q, k, v, out, lse, do, dq, dk, dv, w.softmax_scale, ws, rg)]
+    overlapped, in_line = [], []
+    for d in range(1, n_div):
+        overlapped += [P.instr_comm_launch(2 * d, lists[d], k_far, k), P.instr_comm_launch(2 * d + 1, lists[d], v_far, v)]
+    for d in range(n_div):
+        if d > 0:
+            overlapped += [P.instr_comm_wait(2 * d), P.instr_comm_wait(2 * d + 1)]
+            in_line += [P.instr_copy(lists[d], k_far, k), P.instr_copy(lists[d], v_far, v)]
+        overlapped.append(fwd[d])
+        in_line.append(fwd[d])
+    side = torch.cuda.Stream()
+    res = dict(workload=f"config 5 share as {n_div} divisions; {moved} bytes of KV blocks arrive by transfers", instructions=len(overlapped) + len(tail))
+    for name, prog in (("transfers_on_second_stream_ms", P.Program(overlapped + tail)), ("copies_in_line_ms", P.Program(in_line + tail))):
+        prog.run(side)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            prog.run(side)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = round(e0.elapsed_time(e1) / steps, 3)
     return res
 
 

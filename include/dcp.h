@@ -221,6 +221,47 @@ dcp_status_t dcp_copy_list_destroy(dcp_copy_list_t* list);
 dcp_status_t dcp_blockwise_copy(dcp_copy_list_t* list, const void* src, int64_t src_row_stride,
                                 void* dst, int64_t dst_row_stride, int64_t row_bytes, void* stream);
 
+/* Execution plans (Sec. 5: "an execution plan consists of a sequence of such instructions ... sequentially executed
+ * by the executor"; Sec. 4.3: the transfer of one division overlaps the computation of another).  The five instruction
+ * types of Sec. 5 map to ops: Blockwise Attention (forward, backward), Blockwise Reduction (LSE merge of partial
+ * outputs; plain sum of gradient partials), Blockwise Copy, Comm.Launch and Comm.Wait.  With one device a transfer is
+ * a Blockwise Copy handed to a second stream: Comm.Launch starts it after everything issued before it and returns at
+ * once, Comm.Wait makes the compute stream wait for it.
+ * Fields used per op (others ignored):
+ *   ATTN_FWD     plan, tensors                       -> dcp_block_attn_fwd
+ *   ATTN_BWD     plan, tensors, workspace(+bytes)    -> dcp_block_attn_bwd
+ *   MERGE        plan, o_part, lse_part, tensors.{out, o_stride_t, o_stride_h, lse, hq, d, dtype} -> dcp_merge_partials
+ *   COPY         copy_list, src, src_row_stride, dst, dst_row_stride, row_bytes -> dcp_blockwise_copy
+ *   SUM          parts, n_parts, parts_dtype, dst, dst_dtype, n_elems -> dcp_sum_partials
+ *   COMM_LAUNCH  comm_id + the COPY fields;  COMM_WAIT  comm_id
+ * The program copies the instruction array; plans, copy lists and buffers stay the caller's and must outlive it. */
+typedef enum { DCP_OP_ATTN_FWD = 0, DCP_OP_ATTN_BWD = 1, DCP_OP_MERGE = 2, DCP_OP_COPY = 3, DCP_OP_SUM = 4,
+               DCP_OP_COMM_LAUNCH = 5, DCP_OP_COMM_WAIT = 6 } dcp_op_t;
+typedef struct {
+  int32_t op, comm_id;
+  dcp_plan_t* plan;
+  dcp_tensors_t tensors;
+  void* workspace;
+  size_t workspace_bytes;
+  const void* o_part;
+  const float* lse_part;
+  dcp_copy_list_t* copy_list;
+  const void* src;
+  void* dst;
+  int64_t src_row_stride, dst_row_stride, row_bytes;
+  const void* parts[8];
+  int32_t n_parts, parts_dtype, dst_dtype;
+  int64_t n_elems;
+} dcp_instr_t;
+typedef struct dcp_program dcp_program_t;
+/* DCP_ERR_INVALID_ARG: unknown op, a missing handle, a transfer id launched twice or waited for before its launch. */
+dcp_status_t dcp_program_create(dcp_program_t** program, const dcp_instr_t* instrs_host, int64_t n);
+dcp_status_t dcp_program_destroy(dcp_program_t* program);
+/* Issues every instruction (asynchronous).  compute_stream runs everything except the transfers, which run on
+ * comm_stream (a different stream if the program has any).  On return the compute stream also waits for every
+ * transfer that no Comm.Wait covered, so synchronising it is enough.  The first error stops the walk and is returned. */
+dcp_status_t dcp_program_run(dcp_program_t* program, void* compute_stream, void* comm_stream);
+
 /* Communication volume of a placement (host only; Sec. 4.1, the volume of a configuration, and Sec. 4.2, the
  * connectivity metric of the hypergraph whose hyperedges join each data block to the computation blocks that
  * consume it or contribute to it).  A table row is one computation block (all heads): it consumes Q block q_blk

@@ -29,9 +29,29 @@ class Tensors(ctypes.Structure):
     ]
 
 
+class Instr(ctypes.Structure):
+    """dcp_instr_t"""
+    _fields_ = [
+        ("op", ctypes.c_int32), ("comm_id", ctypes.c_int32),
+        ("plan", vp),
+        ("tensors", Tensors),
+        ("workspace", vp), ("workspace_bytes", ctypes.c_size_t),
+        ("o_part", vp), ("lse_part", vp),
+        ("copy_list", vp),
+        ("src", vp), ("dst", vp),
+        ("src_row_stride", ctypes.c_int64), ("dst_row_stride", ctypes.c_int64), ("row_bytes", ctypes.c_int64),
+        ("parts", vp * 8),
+        ("n_parts", ctypes.c_int32), ("parts_dtype", ctypes.c_int32), ("dst_dtype", ctypes.c_int32),
+        ("n_elems", ctypes.c_int64),
+    ]
+
+
 _SIGS = {
     "dcp_build_block_table": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, i32p, ctypes.c_int64, i64p]),
     "dcp_count_pairs": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, i64p]),
+    "dcp_program_create": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.POINTER(Instr), ctypes.c_int64]),
+    "dcp_program_destroy": (ctypes.c_int, [vp]),
+    "dcp_program_run": (ctypes.c_int, [vp, vp, vp]),
     "dcp_comm_volume": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, i32p, ctypes.c_int32,
                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, i64p, i64p, i64p, i64p, i64p]),
     "dcp_plan_create": (ctypes.c_int, [ctypes.POINTER(vp), i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, ctypes.c_int32]),

@@ -256,6 +256,127 @@ def dcp_blockwise_copy(copy_list, src, dst):
     _check(_lib.load().dcp_blockwise_copy(copy_list.handle, src.data_ptr(), st_s, dst.data_ptr(), st_d, rb_s, _stream()))
 
 
+# ---------------------------------------------------------------------------------------------
+# execution plans: instruction constructors (they fill a dcp_instr_t and keep the tensors alive) and Program
+OP_ATTN_FWD, OP_ATTN_BWD, OP_MERGE, OP_COPY, OP_SUM, OP_COMM_LAUNCH, OP_COMM_WAIT = range(7)
+
+
+def _row_view(t):
+    assert t.dim() >= 1 and (t.dim() == 1 or t[0].is_contiguous()), "rows must be contiguous"
+    row_bytes = (t[0].numel() if t.dim() > 1 else 1) * t.element_size()
+    stride = (t.stride(0) if t.shape[0] > 1 else (t[0].numel() if t.dim() > 1 else 1)) * t.element_size()
+    return row_bytes, stride
+
+
+def instr_attn_fwd(plan, q, k, v, out, lse, softmax_scale, attn_ranges=None, impl=DCP_IMPL_AUTO):
+    ins = _lib.Instr()
+    ins.op, ins.plan = OP_ATTN_FWD, plan.handle
+    ts = _descr(q, k, v, softmax_scale, attn_ranges, impl)
+    if plan.n_slots or out.dim() == 4:
+        ts.out = out.data_ptr()
+    else:
+        _set(ts, "out", out)
+    ts.lse = lse.data_ptr()
+    ins.tensors = ts
+    ins._keep = (plan, q, k, v, out, lse, attn_ranges)
+    return ins
+
+
+def instr_attn_bwd(plan, q, k, v, out, lse, dout, dq, dk, dv, softmax_scale, workspace, attn_ranges=None, impl=DCP_IMPL_AUTO):
+    ins = _lib.Instr()
+    ins.op, ins.plan = OP_ATTN_BWD, plan.handle
+    ts = _descr(q, k, v, softmax_scale, attn_ranges, impl)
+    for name, t in (("out", out), ("dout", dout), ("dq", dq), ("dk", dk), ("dv", dv)):
+        _set(ts, name, t)
+    ts.lse = lse.data_ptr()
+    ins.tensors = ts
+    ins.workspace, ins.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    ins._keep = (plan, q, k, v, out, lse, dout, dq, dk, dv, workspace, attn_ranges)
+    return ins
+
+
+def instr_merge(plan, o_part, lse_part, out, lse):
+    ins = _lib.Instr()
+    ins.op, ins.plan = OP_MERGE, plan.handle
+    ins.o_part, ins.lse_part = o_part.data_ptr(), lse_part.data_ptr()
+    ts = Tensors()
+    ts.hq, ts.d, ts.dtype = out.shape[1], out.shape[2], _dtype_code(out)
+    _set(ts, "out", out)
+    ts.lse = lse.data_ptr()
+    ins.tensors = ts
+    ins._keep = (plan, o_part, lse_part, out, lse)
+    return ins
+
+
+def _fill_copy(ins, copy_list, src, dst):
+    rb_s, st_s = _row_view(src)
+    rb_d, st_d = _row_view(dst)
+    assert rb_s == rb_d and src.shape[0] == copy_list.src_rows and dst.shape[0] == copy_list.dst_rows
+    ins.copy_list, ins.src, ins.dst = copy_list.handle, src.data_ptr(), dst.data_ptr()
+    ins.src_row_stride, ins.dst_row_stride, ins.row_bytes = st_s, st_d, rb_s
+    ins._keep = (copy_list, src, dst)
+
+
+def instr_copy(copy_list, src, dst):
+    ins = _lib.Instr()
+    ins.op = OP_COPY
+    _fill_copy(ins, copy_list, src, dst)
+    return ins
+
+
+def instr_sum(parts, dst):
+    ins = _lib.Instr()
+    ins.op, ins.n_parts, ins.parts_dtype = OP_SUM, len(parts), _dtype_code(parts[0])
+    for i, p in enumerate(parts):
+        ins.parts[i] = p.data_ptr()
+    ins.dst, ins.dst_dtype, ins.n_elems = dst.data_ptr(), _dtype_code(dst), dst.numel()
+    ins._keep = (list(parts), dst)
+    return ins
+
+
+def instr_comm_launch(comm_id, copy_list, src, dst):
+    """On one device the transfer is a Blockwise Copy on the second stream."""
+    ins = _lib.Instr()
+    ins.op, ins.comm_id = OP_COMM_LAUNCH, comm_id
+    _fill_copy(ins, copy_list, src, dst)
+    return ins
+
+
+def instr_comm_wait(comm_id):
+    ins = _lib.Instr()
+    ins.op, ins.comm_id = OP_COMM_WAIT, comm_id
+    return ins
+
+
+class Program:
+    """An execution plan: instructions run in order by dcp_program_run."""
+
+    def __init__(self, instrs):
+        self._instrs = list(instrs)                      # keeps tensors, plans and copy lists alive
+        arr = (_lib.Instr * max(1, len(self._instrs)))()
+        for i, ins in enumerate(self._instrs):
+            ctypes.memmove(ctypes.byref(arr[i]), ctypes.byref(ins), ctypes.sizeof(_lib.Instr))
+        h = ctypes.c_void_p()
+        _check(_lib.load().dcp_program_create(ctypes.byref(h), arr, len(self._instrs)))
+        self.handle = h
+
+    def run(self, comm_stream=None):
+        """Compute stream = torch's current stream; comm_stream: a torch.cuda.Stream (needed if the plan has transfers)."""
+        cs = comm_stream.cuda_stream if comm_stream is not None else _stream()
+        _check(_lib.load().dcp_program_run(self.handle, _stream(), cs))
+
+    def close(self):
+        if getattr(self, "handle", None):
+            _lib.load().dcp_program_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 KERNEL_IDS = dict(fwd=0, merge=1, delta=2, dq=3, dkv=4, sum=5, copy=6)
 
 

@@ -322,3 +322,88 @@ def test_block_buffer_with_absent_blocks_and_partial_slots():
     # drop every row that has q_blk 2 or kv_blk 5: block 2 produces no output, block 5 receives no gradient
     sub = table[(table[:, 0] != 2) & (table[:, 1] != 5)]
     _buffer_case(w, sub, 0, rng, absent_ok=True)
+
+
+def test_execution_plan_with_divisions_and_transfers():
+    """Sec. 5 / Sec. 4.3: an execution plan of three divisions.  Division 0 attends with the KV blocks that are already
+    in the KV block buffer; the blocks divisions 1 and 2 need first are moved in by Comm.Launch (a Blockwise Copy on
+    the second stream) and awaited by Comm.Wait right before their attention.  Every division writes partial slots,
+    a Blockwise Reduction merges them, a backward instruction follows.  Buffer rows start poisoned, so an attention
+    that ran before its transfer had landed would produce NaN."""
+    import torch
+    import paper_2510_10620_amd as P
+    from oracle import blockbuf as BB
+    rng = np.random.default_rng(47)
+    w = W.custom_workload("exec", [330, 200, 90], 64, 4, 2, 128, "bf16", W.MaskSpec("causal"), seed=48, input_scale=0.5)
+    tensors = W.make_tensors(w)
+    table = H.oracle_table(w)
+    part = OB.block_partition(w.cu_seqlens, w.block_size)
+    bs, bl = part["blk_start"], part["blk_end"] - part["blk_start"]
+    nb, B, T = len(bs), w.block_size, w.total_tokens
+    n_div = 3
+    slot, n_slots, _ = W.deal_divisions(table[:, 0], n_div, 9)
+    div = np.zeros(len(table), dtype=np.int64)
+    # recover each row's division from its slot: deal_divisions numbers slots per (division, q_blk)
+    perm = np.random.default_rng(9).permutation(len(table))
+    div[perm] = np.arange(len(table)) % n_div
+    assert len(set(zip(div.tolist(), table[:, 0].tolist()))) == n_slots
+    # KV buffer: permuted slots; a block is "remote" for the first division that uses it unless division 0 does
+    kv_slot = rng.permutation(nb + 1)[:nb].astype(np.int32)
+    q_slot = np.arange(nb, dtype=np.int32)                      # Q side stays in packed order (slot b = block b)
+    first_div = np.full(nb, n_div)
+    for d, kb in zip(div, table[:, 1]):
+        first_div[kb] = min(first_div[kb], d)
+    nan16 = np.uint16(0x7FC0)
+    kbuf = BB.gather_blocks(tensors["k"], bs, bl, np.where(first_div == 0, kv_slot, -1), nb + 1, B, fill=nan16)
+    vbuf = BB.gather_blocks(tensors["v"], bs, bl, np.where(first_div == 0, kv_slot, -1), nb + 1, B, fill=nan16)
+    qbuf = BB.gather_blocks(tensors["q"], bs, bl, q_slot, nb, B, fill=nan16)
+    dobuf = BB.gather_blocks(tensors["dout"], bs, bl, q_slot, nb, B, fill=nan16)
+    tq, tk, tv, tdo = (H.to_torch(w, a) for a in (qbuf, kbuf, vbuf, dobuf))
+    k_far, v_far = H.to_torch(w, tensors["k"]), H.to_torch(w, tensors["v"])     # where remote blocks come from
+    rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+    o_part = torch.full((n_slots, B, w.hq, w.d), float("nan"), dtype=tq.dtype, device="cuda")
+    lse_part = torch.full((n_slots, w.hq, B), float("nan"), dtype=torch.float32, device="cuda")
+    out = torch.full((nb * B, w.hq, w.d), float("nan"), dtype=tq.dtype, device="cuda")
+    lse = torch.full((w.hq, nb * B), float("nan"), dtype=torch.float32, device="cuda")
+    dq = torch.zeros_like(out)
+    dk = torch.zeros(((nb + 1) * B, w.hkv, w.d), dtype=tq.dtype, device="cuda")
+    dv = torch.zeros_like(dk)
+
+    def make_plan(rows):
+        pl = P.dcp_plan_create(w.cu_seqlens, B, table[rows], slot[rows], n_slots)
+        P.dcp_plan_set_block_buffers(pl, q_slot, nb, kv_slot, nb + 1)
+        return pl
+    full = make_plan(np.arange(len(table)))
+    plain = P.dcp_plan_create(w.cu_seqlens, B, table)               # backward of the whole table, no slots
+    P.dcp_plan_set_block_buffers(plain, q_slot, nb, kv_slot, nb + 1)
+    ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plain, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
+    instrs = []
+    for d in range(1, n_div):                                         # launch every transfer up front
+        need = np.nonzero(first_div == d)[0]
+        entries = np.stack([bs[need], kv_slot[need].astype(np.int64) * B, bl[need]], axis=1).astype(np.int32)
+        cl = P.CopyList(entries, T, (nb + 1) * B)
+        instrs.append(P.instr_comm_launch(2 * d, cl, k_far, tk))
+        instrs.append(P.instr_comm_launch(2 * d + 1, cl, v_far, tv))
+    for d in range(n_div):
+        if d > 0:
+            instrs += [P.instr_comm_wait(2 * d), P.instr_comm_wait(2 * d + 1)]
+        instrs.append(P.instr_attn_fwd(make_plan(np.nonzero(div == d)[0]), tq, tk, tv, o_part, lse_part, w.softmax_scale, rg))
+    instrs.append(P.instr_merge(full, o_part, lse_part, out, lse))
+    instrs.append(P.instr_attn_bwd(plain, tq, tk, tv, out, lse, tdo, dq, dk, dv, w.softmax_scale, ws, rg))
+    prog = P.Program(instrs)
+    side = torch.cuda.Stream()
+    for rep in range(2):                                              # a plan is replayed for every layer
+        if rep == 1:                                                  # poison the remote blocks again
+            tk.copy_(H.to_torch(w, kbuf)); tv.copy_(H.to_torch(w, vbuf))
+            torch.cuda.synchronize()
+        prog.run(side)
+        torch.cuda.synchronize()
+        got = dict(out=BB.scatter_blocks(H.from_torch(out), bs, bl, q_slot, B, T),
+                   lse=BB.scatter_rows_hT(H.from_torch(lse), bs, bl, q_slot, B, T),
+                   dq=BB.scatter_blocks(H.from_torch(dq), bs, bl, q_slot, B, T),
+                   dk=BB.scatter_blocks(H.from_torch(dk), bs, bl, kv_slot, B, T),
+                   dv=BB.scatter_blocks(H.from_torch(dv), bs, bl, kv_slot, B, T))
+        H.check(w, got, H.oracle_full(w, tensors, table), ALL, f"execution plan, replay {rep}")
+    # a program with transfers refuses to run on one stream
+    with pytest.raises(P.DcpError):
+        prog.run(None)

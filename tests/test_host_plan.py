@@ -240,3 +240,27 @@ def test_comm_volume_errors():
     with pytest.raises(P.DcpError) as e:
         P.dcp_comm_volume(cu, 32, table, ok["blk_dev"], ok["comp_dev"], 0, 1, 1, 1)
     assert e.value.status == P.DCP_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ execution plans (host-side validation)
+def test_program_validation():
+    from paper_2510_10620_amd import _lib as L
+    P.Program([]).close()
+    w1, w2 = P.instr_comm_wait(0), P.instr_comm_wait(3)
+    for bad in ([w1],):                                   # wait before any launch
+        with pytest.raises(P.DcpError) as e:
+            P.Program(bad)
+        assert e.value.status == P.DCP_ERR_INVALID_ARG
+    ins = L.Instr()
+    ins.op = 99
+    with pytest.raises(P.DcpError):
+        P.Program([ins])
+    ins = L.Instr()
+    ins.op = P.OP_ATTN_FWD                                # no plan
+    with pytest.raises(P.DcpError):
+        P.Program([ins])
+    ins = L.Instr()
+    ins.op, ins.comm_id = P.OP_COMM_LAUNCH, 0             # no copy list
+    with pytest.raises(P.DcpError):
+        P.Program([ins])
+    assert w2.comm_id == 3
