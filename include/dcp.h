@@ -180,7 +180,9 @@ dcp_status_t dcp_merge_partials(dcp_plan_t* plan, const void* o_part, const floa
  * t->dout (hq, d, dtype, strides); writes delta device float [Hq,T]. */
 dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_tokens, float* delta, void* stream);
 
-/* Bytes of device workspace dcp_block_attn_bwd needs for this plan and shape. */
+/* Bytes of device workspace dcp_block_attn_bwd needs for this plan and shape: delta and the rescaled LSE, each
+ * float [Hq, rows of the Q-type buffers], plus, for tables with RANGES rows, 32 bytes per 32-row tile of every block
+ * (bounds of the rows' range arrays, which let the dK/dV kernel pass over query tiles that see none of its keys). */
 size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype);
 
 /* Blockwise Attention, backward (the mirrored instruction stream of Sec. 5; gradients of blocks
