@@ -121,14 +121,26 @@ __device__ __forceinline__ void fwd_tile64(FwdState<NQ>& st, const char* k_lds, 
     for (int nq = 0; nq < NQ; nq++)
 #pragma unroll
       for (int r = 0; r < 16; r++) s[kt][nq][r] = 0.f;
+  // K fragments are requested four k-steps ahead of the MFMAs that use them
+  constexpr int PF = 4;
+  bf16x8 ka[8][2];
 #pragma unroll
-  for (int ksd = 0; ksd < 8; ksd++)
+  for (int ksd = 0; ksd < PF; ksd++)
 #pragma unroll
-    for (int kt = 0; kt < 2; kt++) {
-      const bf16x8 a = frag_rm(k_lds, st.fa, 32 * kt, ksd);
+    for (int kt = 0; kt < 2; kt++) ka[ksd][kt] = frag_rm(k_lds, st.fa, 32 * kt, ksd);
 #pragma unroll
-      for (int nq = 0; nq < NQ; nq++) s[kt][nq] = mfma(a, st.qf[nq][ksd], s[kt][nq]);
+  for (int ksd = 0; ksd < 8; ksd++) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (ksd + PF < 8) {
+#pragma unroll
+      for (int kt = 0; kt < 2; kt++) ka[ksd + PF][kt] = frag_rm(k_lds, st.fa, 32 * kt, ksd + PF);
     }
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+      for (int nq = 0; nq < NQ; nq++) s[kt][nq] = mfma(ka[ksd][kt], st.qf[nq][ksd], s[kt][nq]);
+  }
+  __builtin_amdgcn_sched_barrier(0);
   bf16x8 p[2][NQ][2];
 #pragma unroll
   for (int nq = 0; nq < NQ; nq++) {
