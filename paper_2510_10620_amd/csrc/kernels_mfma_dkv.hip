@@ -100,91 +100,97 @@ struct QIter {
   }
 };
 
+// Fragment addresses from two registers: the swizzle makes every other address an XOR of these with a constant.
+struct FragAddr2 {
+  int rm0, tr00;
+  __device__ __forceinline__ void init(int lane) {
+    const int li = lane & 31, lh = lane >> 5;
+    rm0 = tile_off(li, lh);
+    const int j = lane & 15, blk = lane >> 4, h = blk >> 1;
+    const int col = 16 * (blk & 1) + 4 * (j & 3);
+    tr00 = tile_off(4 * h + (j >> 2), col >> 3) + (col & 7) * 2;
+  }
+};
+__device__ __forceinline__ bf16x8 frag_rm2(const char* tile, const FragAddr2& fa, int row0, int ks) {
+  return as_frag(*(const uint4*)(tile + row0 * kRowBytes + (fa.rm0 ^ (ks << 5))));
+}
+__device__ __forceinline__ bf16x8 frag_tr2(const char* tile, const FragAddr2& fa, int row0, int dt) {
+  typedef __attribute__((address_space(3))) s16x4* lds_p;
+  const int a0 = fa.tr00 ^ (dt << 6);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(tile + row0 * kRowBytes + a0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(tile + row0 * kRowBytes + (a0 ^ 0x820)));
+  s16x8 v;
+  v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3]; v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Bits [0, x - base) of a 32-key window that starts at key `base`: the keys of the window below key x.
+__device__ __forceinline__ uint32_t keys_below(int x, int base) {
+  const int n = min(max(x, base), base + 32) - base;   // 0..32, no overflow for any x
+  return n >= 32 ? 0xffffffffu : (1u << n) - 1u;
+}
+
+// What a wave keeps for the whole kernel: its 32 keys' K and V fragments and the dK^T / dV^T accumulators (192
+// registers).  Two workgroups share a CU (two waves per SIMD), so everything else has to fit in 64.
 struct DkvState {
   bf16x8 kf[8], vf[8];
   f32x16 dk[4], dv[4];
-  int kj;
-  FragAddr fa;
-  TileDma dmaq, dmao;
 };
 
+// One 32-query sub-tile against the wave's 32 keys.  Operands are read where they are used: the SIMD's other wave
+// hides the latency.  Everything that depends on the lane alone (fragment addresses, the key index, the rows'
+// LSE / delta addresses) is recomputed in every call from an opaque copy of the lane number, or the compiler
+// hoists two dozen loop-invariant registers out of the query loop and spills.
 template <bool RANGES>
 __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int qt, int qs32, int q1, int kind,
-                                            int k_end, float c_log2, int lane, bool MASK) {
+                                            int wk_lo, int k_end, float c_log2, bool MASK) {
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
   const int lh = lane >> 5;
+  const int kj = wk_lo + (lane & 31);   // may lie past k_end: masked, never stored
   const char* q_lds = stage;
   const char* do_lds = stage + kTileBytes;
+  FragAddr2 fa;
+  fa.init(lane);
   f32x16 s, dp;
 #pragma unroll
   for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
-  // operand fragments are requested four k-steps ahead of the MFMAs that use them: one exposed LDS round
-  // trip per sub-tile, not one per k-step (left alone, the compiler reuses two registers and waits for every pair)
-  bf16x8 qa[8], da[8];
-  // rows of the C tile are queries 8a + 4 lh + b: their LSE / delta come from LDS (broadcast reads), requested
-  // first so that nothing queued later stands between them and the exponentials
-  const float* lse_lds = (const float*)(stage + kStageLse) + 32 * qt + 4 * lh;
-  const float* dl_lds = (const float*)(stage + kStageDelta) + 32 * qt + 4 * lh;
-  float4 l4[4], d4[4];
-#pragma unroll
-  for (int a = 0; a < 4; a++) {
-    l4[a] = *(const float4*)(lse_lds + 8 * a);
-    d4[a] = *(const float4*)(dl_lds + 8 * a);
-  }
-#pragma unroll
-  for (int ksd = 0; ksd < 4; ksd++) {
-    qa[ksd] = frag_rm(q_lds, st.fa, 32 * qt, ksd);
-    da[ksd] = frag_rm(do_lds, st.fa, 32 * qt, ksd);
-  }
-  // transposed operands of the second half (dO^T, Q^T; two groups of 16 queries): the first group is requested
-  // under the score MFMAs, the second under the exponentials
-  bf16x8 dot[2][4], qt_[2][4];
 #pragma unroll
   for (int ksd = 0; ksd < 8; ksd++) {
-    __builtin_amdgcn_sched_barrier(0);
-    if (ksd + 4 < 8) {
-      qa[ksd + 4] = frag_rm(q_lds, st.fa, 32 * qt, ksd + 4);
-      da[ksd + 4] = frag_rm(do_lds, st.fa, 32 * qt, ksd + 4);
-    } else {
-      dot[0][ksd - 4] = frag_tr(do_lds, st.fa, 32 * qt, ksd - 4);
-      qt_[0][ksd - 4] = frag_tr(q_lds, st.fa, 32 * qt, ksd - 4);
-    }
-    s = mfma(qa[ksd], st.kf[ksd], s);
-    dp = mfma(da[ksd], st.vf[ksd], dp);
+    s = mfma(frag_rm2(q_lds, fa, 32 * qt, ksd), st.kf[ksd], s);
+    dp = mfma(frag_rm2(do_lds, fa, 32 * qt, ksd), st.vf[ksd], dp);
   }
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int dt = 0; dt < 4; dt++) {
-    dot[1][dt] = frag_tr(do_lds, st.fa, 32 * qt + 16, dt);
-    qt_[1][dt] = frag_tr(q_lds, st.fa, 32 * qt + 16, dt);
-  }
-  __builtin_amdgcn_sched_barrier(0);
   if (MASK) {
-    // element r = 4a + b is (query qs32 + 8a + 4 lh + b, key kj); queries past the block end are
-    // clamped duplicates of its last row and must not count
-    const int qb0 = qs32 + 4 * lh;
-    const bool kok = st.kj < k_end;
+    // Lane l works out, once, which of the wave's 32 keys query row (l & 31) of the sub-tile sees, as a bit mask
+    // (bit j = key wk_lo + j).  Element r = 4a + b of the score tile is (query row 8a + 4 lh + b, key lane & 31), so
+    // its 64-lane condition is the pair {mask of row 8a + b, mask of row 8a + 4 + b}: two lane reads and one select
+    // per element instead of the range comparisons.  Rows past the block end (clamped duplicates of its last
+    // row) and keys past the tile end see nothing.
+    const int row = lane & 31;
+    const int q = qs32 + row;
+    int lo1 = 0, hi1 = kind == 1 ? q + 1 : INT32_MAX, lo2 = 0, hi2 = 0;   // NONE: every key; CAUSAL: keys up to the query
     if (RANGES && kind == 2) {
-      const int4* rg_lds = (const int4*)(stage + kStageRanges) + 32 * qt + 4 * lh;
+      asm volatile("" ::: "memory");   // keeps the read inside the branch
+      const int4 rg = ((const int4*)(stage + kStageRanges))[32 * qt + row];
+      lo1 = rg.x; hi1 = rg.y; lo2 = rg.z; hi2 = rg.w;
+    }
+    uint32_t m = (keys_below(hi1, wk_lo) & ~keys_below(lo1, wk_lo)) | (keys_below(hi2, wk_lo) & ~keys_below(lo2, wk_lo));
+    m &= keys_below(k_end, wk_lo);
+    m = q < q1 ? m : 0u;
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int4 rg = rg_lds[8 * (r / 4) + (r % 4)];
-        const int q = qb0 + 8 * (r / 4) + (r % 4);
-        const bool vis = kok & (q < q1) & (((st.kj >= rg.x) & (st.kj < rg.y)) | ((st.kj >= rg.z) & (st.kj < rg.w)));
-        s[r] = vis ? s[r] : -INFINITY;
-      }
-    } else {
-      const int kcmp = kind == 1 ? st.kj : INT32_MIN;   // causal: key <= query
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int q = qb0 + 8 * (r / 4) + (r % 4);
-        const bool vis = kok & (q < q1) & (kcmp <= q);
-        s[r] = vis ? s[r] : -INFINITY;
-      }
+    for (int r = 0; r < 16; r++) {
+      const int r0 = 8 * (r / 4) + (r % 4);
+      const uint64_t cond = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)m, r0) |
+                            ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)m, r0 + 4) << 32);
+      s[r] = __builtin_amdgcn_inverse_ballot_w64(cond) ? s[r] : -INFINITY;
     }
   }
+  const float* lse_lds = (const float*)(stage + kStageLse) + 32 * qt + 4 * lh;
+  const float* dl_lds = (const float*)(stage + kStageDelta) + 32 * qt + 4 * lh;
 #pragma unroll
   for (int a = 0; a < 4; a++) {
-    const float lv[4] = {l4[a].x, l4[a].y, l4[a].z, l4[a].w}, dv4[4] = {d4[a].x, d4[a].y, d4[a].z, d4[a].w};
+    const float4 l4 = *(const float4*)(lse_lds + 8 * a), d4 = *(const float4*)(dl_lds + 8 * a);
+    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
     for (int b = 0; b < 4; b++) {
       const int r = 4 * a + b;
@@ -198,18 +204,17 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
     const bf16x8 pb = pack_frag(s, c), dsb = pack_frag(dp, c);
 #pragma unroll
     for (int dt = 0; dt < 4; dt++) {
-      st.dv[dt] = mfma(dot[c][dt], pb, st.dv[dt]);
-      st.dk[dt] = mfma(qt_[c][dt], dsb, st.dk[dt]);
+      st.dv[dt] = mfma(frag_tr2(do_lds, fa, 32 * qt + 16 * c, dt), pb, st.dv[dt]);
+      st.dk[dt] = mfma(frag_tr2(q_lds, fa, 32 * qt + 16 * c, dt), dsb, st.dk[dt]);
     }
   }
 }
 
 // RANGES = false: the table has no RANGES row; everything that serves them is compiled out.
 template <bool RANGES>
-__global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t) {
+__global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t) {
   constexpr int TK = 128;
-  __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char stage1[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char stages[2 * kStageBytes];   // double buffer
 
   int item, hk;
   if (!decode_wg(g.n_items, t.hkv, 1, &item, &hk)) return;
@@ -229,13 +234,9 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   const int wk_lo = k_lo + wrow0, wk_hi = wk_lo + w_rows - 1;
 
   DkvState st;
-  st.fa.init(lane);
-  st.dmaq.init(wave, lane, t.q_st);
-  st.dmao.init(wave, lane, t.do_st);
   const bool kvalid = wrow0 + li < n_rows;
-  st.kj = k_lo + wrow0 + li;                       // may lie past k_end: masked, never stored
   {
-    const int kl = min(st.kj, k_end - 1);
+    const int kl = min(wk_lo + li, k_end - 1);
     const bf16_t* kp = (const bf16_t*)t.k + (int64_t)(kl + koff) * t.k_st + (int64_t)hk * t.k_sh + 8 * lh;
     const bf16_t* vp = (const bf16_t*)t.v + (int64_t)(kl + koff) * t.v_st + (int64_t)hk * t.v_sh + 8 * lh;
 #pragma unroll
@@ -254,8 +255,8 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
   auto issue = [&](char* stage) {
     const int head = hk * G + it.hh;
     const int last = it.q1 - 1;
-    st.dmaq.load(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, it.qs + it.moff, last + it.moff, wave);
-    st.dmao.load(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, it.qs + it.moff, last + it.moff, wave);
+    tile_dma_lean<4>(stage, (const bf16_t*)t.q + (int64_t)head * t.q_sh, (int)t.q_st * 2, it.qs + it.moff, last + it.moff, wave);
+    tile_dma_lean<4>(stage + kTileBytes, (const bf16_t*)t.dout + (int64_t)head * t.do_sh, (int)t.do_st * 2, it.qs + it.moff, last + it.moff, wave);
     const int qrow = min(it.qs + lane, last);   // packed index: the range array is not a data block
     const int qmem = qrow + it.moff;
     if (wave == 0) dma4((unsigned)qmem * 4u, uni_ptr(t.lse2 + (int64_t)head * t.q_rows), lds_addr(stage + kStageLse));
@@ -266,18 +267,21 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
       dma16((unsigned)(lane & 3) * 16u, uni_ptr(t.qbounds + (int64_t)(it.t32 + 2 * it.jt) * 8), lds_addr(stage + kStageBounds));
   };
   bool have = it.next(k_lo, k_end);
-  if (have) issue(stage0);
+  if (have) issue(stages);
   DCP_WAIT_VMCNT(0);
   __syncthreads();
-  auto step = [&](const char* cur, char* nxt) {
+  // one copy of the sub-tile code for both buffers and both halves of a tile: the accumulators keep their registers
+  int buf = 0;
+  while (have) {
+    const char* cur = stages + buf;
     const int qs = it.qs, q1 = it.q1, kind = it.kind;
     have = it.next(k_lo, k_end);
-    if (have) issue(nxt);
+    if (have) issue(stages + (buf ^ kStageBytes));
     if (w_rows > 0) {
-#pragma unroll
+#pragma unroll 1
       for (int qt = 0; qt < 2; qt++) {
         const int qs32 = qs + 32 * qt;
-        if (qs32 >= q1) continue;
+        if (qs32 >= q1) break;
         const bool whole = qs32 + 32 <= q1 && w_rows == 32;
         int cls = kPartial;
         if (kind == 0) cls = whole ? kFull : kPartial;
@@ -294,20 +298,16 @@ __global__ __launch_bounds__(256, 1) void mfma_dkv_kernel(DevGroup g, KTensors t
           if (!qb.may_see(wk_lo, wk_hi + 1)) cls = kSkip;
           else if (whole && qb.all_see(wk_lo, wk_hi + 1)) cls = kFull;
         }
-        if (cls != kSkip) dkv_subtile<RANGES>(st, cur, qt, qs32, q1, kind, k_end, c_log2, lane, cls == kPartial);
+        if (cls != kSkip) dkv_subtile<RANGES>(st, cur, qt, qs32, q1, kind, wk_lo, k_end, c_log2, cls == kPartial);
       }
     }
     DCP_WAIT_VMCNT(0);
     __syncthreads();
-  };
-  while (have) {
-    step(stage0, stage1);
-    if (!have) break;
-    step(stage1, stage0);
+    buf ^= kStageBytes;
   }
   if (!kvalid) return;
-  bf16_t* dkp = (bf16_t*)t.dk + (int64_t)(st.kj + koff) * t.dk_st + (int64_t)hk * t.dk_sh;
-  bf16_t* dvp = (bf16_t*)t.dv + (int64_t)(st.kj + koff) * t.dv_st + (int64_t)hk * t.dv_sh;
+  bf16_t* dkp = (bf16_t*)t.dk + (int64_t)(wk_lo + li + koff) * t.dk_st + (int64_t)hk * t.dk_sh;
+  bf16_t* dvp = (bf16_t*)t.dv + (int64_t)(wk_lo + li + koff) * t.dv_st + (int64_t)hk * t.dv_sh;
 #pragma unroll
   for (int dt = 0; dt < 4; dt++)
 #pragma unroll

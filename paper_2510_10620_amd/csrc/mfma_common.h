@@ -175,6 +175,22 @@ struct TileDmaT {
   }
 };
 
+// The same copy with nothing kept in registers between calls (for kernels that have none to spare): the lane
+// offsets are recomputed from an opaque copy of the lane number at every call.
+template <int PW>
+__device__ __forceinline__ void tile_dma_lean(char* tile, const bf16_t* base, int sb, int row_start, int row_last, int wave) {
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
+  const void* b = uni_ptr((const char*)base + (int64_t)row_start * sb);
+  const unsigned l0 = lds_addr(tile) + wave * PW * 1024;
+  const int lim = row_last - row_start;
+#pragma unroll
+  for (int u = 0; u < PW; u++) {
+    const int row = TileDmaT<PW>::row_of(wave, lane, u);
+    dma16((unsigned)(min(row, lim) * sb + TileDmaT<PW>::chunk_of(lane, row)), b, l0 + u * 1024);
+  }
+}
+
 typedef TileDmaT<4> TileDma;   // 4 waves per workgroup
 
 // Two half-open key ranges of one query row, clipped to a KV block.
