@@ -135,6 +135,16 @@ typedef enum {
 dcp_status_t dcp_plan_export(const dcp_plan_t* plan, dcp_export_t which, int32_t* dst_host,
                              int64_t capacity, int64_t* n_out);
 
+/* The dK/dV work list of the bf16 MFMA kernels for `hkv` KV heads, for bit-exact host checks: rows
+ * (unit = kv_blk position in the BWDKV CSR, tile = 128-key tile of that block, e0, e1 = the CSR entries
+ * [e0, e1) the piece covers, pslot).  An item that would keep one workgroup busy much longer than its
+ * share of the launch is cut along its table rows into parts; each part has its own pslot >= 0 (a slot
+ * of fp32 partial sums in the backward workspace, which a reduce kernel adds up in slot order) and
+ * unsplit items have pslot -1.  Pieces are listed longest first.  dst_host may be NULL to query the
+ * length; n_items_out receives the number of rows (5 int32 each).  Host only. */
+dcp_status_t dcp_plan_export_dkv_items(dcp_plan_t* plan, int32_t hkv, int32_t* dst_host, int64_t capacity_rows,
+                                       int64_t* n_items_out);
+
 /* ---------------------------------------------------------------------------------------------
  * Tensor descriptor shared by the launching calls.  Unused members are NULL / 0. */
 typedef struct {
@@ -182,7 +192,9 @@ dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_tokens, float* 
 
 /* Bytes of device workspace dcp_block_attn_bwd needs for this plan and shape: delta and the rescaled LSE, each
  * float [Hq, rows of the Q-type buffers], plus, for tables with RANGES rows, 32 bytes per 32-row tile of every block
- * (bounds of the rows' range arrays, which let the dK/dV kernel pass over query tiles that see none of its keys). */
+ * (bounds of the rows' range arrays, which let the dK/dV kernel pass over query tiles that see none of its keys),
+ * plus, for the bf16 MFMA kernels, 128 KiB per KV head for every part of a split dK/dV item (fp32 partial sums, see
+ * dcp_plan_export_dkv_items).  The first call for a given hkv builds and caches the work list in the plan. */
 size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype);
 
 /* Blockwise Attention, backward (the mirrored instruction stream of Sec. 5; gradients of blocks

@@ -135,6 +135,16 @@ def dcp_plan_export(plan, which):
     return out
 
 
+def dcp_plan_export_dkv_items(plan, hkv):
+    """[n_items, 5] int32 rows (unit, tile, e0, e1, pslot) of the MFMA dK/dV work list for `hkv` KV heads."""
+    lib = _lib.load()
+    n = ctypes.c_int64(0)
+    _check(lib.dcp_plan_export_dkv_items(plan.handle, int(hkv), None, 0, ctypes.byref(n)))
+    out = np.zeros((n.value, 5), dtype=np.int32)
+    _check(lib.dcp_plan_export_dkv_items(plan.handle, int(hkv), out.ctypes.data_as(_lib.i32p), n.value, ctypes.byref(n)))
+    return out
+
+
 # ------------------------------------------------------------------ launching calls (torch)
 def _dtype_code(t):
     import torch

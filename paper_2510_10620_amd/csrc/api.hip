@@ -161,15 +161,43 @@ extern "C" dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_toke
                       nullptr, total_tokens, t->hq, t->d, t->dtype, (hipStream_t)stream);
 }
 
-extern "C" size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype) {
-  (void)hkv; (void)d; (void)dtype;
-  if (!plan || hq <= 0) return 0;
-  size_t n = (size_t)hq * (size_t)plan->q_rows * sizeof(float);  // delta [Hq, rows], then lse2 [Hq, rows]
-  n = (n + 255) & ~(size_t)255;
+// Workspace layout: delta [Hq, rows] | lse2 [Hq, rows] | range-bound summaries | partial dK / dV sums of split items.
+struct BwdWorkspace {
+  size_t n_hT, n_bounds, n_part;
+  size_t total() const { return 2 * n_hT + n_bounds + n_part; }
+};
+
+static BwdWorkspace bwd_workspace(dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype) {
+  BwdWorkspace w{};
+  w.n_hT = (size_t)hq * (size_t)plan->q_rows * sizeof(float);
+  w.n_hT = (w.n_hT + 255) & ~(size_t)255;
   // range-bound summaries of every 32-row tile (+1 spare entry), only for tables with RANGES rows
-  size_t nb = plan->has_ranges ? ((size_t)plan->blk_t32.back() + 1) * 8 * sizeof(int32_t) : 0;
-  nb = (nb + 255) & ~(size_t)255;
-  return 2 * n + nb;
+  w.n_bounds = plan->has_ranges ? ((size_t)plan->blk_t32.back() + 1) * 8 * sizeof(int32_t) : 0;
+  w.n_bounds = (w.n_bounds + 255) & ~(size_t)255;
+  if (hkv > 0 && mfma_supports(dtype, d)) w.n_part = mfma_dkv_part_bytes(plan->host_items(2, mfma_dkv_tile(), hkv).n_pslots, hkv);
+  return w;
+}
+
+extern "C" dcp_status_t dcp_plan_export_dkv_items(dcp_plan_t* plan, int32_t hkv, int32_t* dst, int64_t capacity_rows,
+                                                  int64_t* n_items_out) {
+  if (!plan || !n_items_out) return fail(DCP_ERR_INVALID_ARG, "plan or n_items_out is NULL");
+  if (hkv <= 0) return fail(DCP_ERR_INVALID_ARG, "hkv must be positive");
+  const HostItems& hi = plan->host_items(2, mfma_dkv_tile(), hkv);
+  *n_items_out = (int64_t)hi.items.size();
+  if (dst) {
+    if (capacity_rows < (int64_t)hi.items.size()) return fail(DCP_ERR_INVALID_ARG, "export capacity too small");
+    for (size_t i = 0; i < hi.items.size(); i++) {
+      const WorkItem& w = hi.items[i];
+      dst[5 * i] = w.unit; dst[5 * i + 1] = w.tile; dst[5 * i + 2] = w.e0; dst[5 * i + 3] = w.e1; dst[5 * i + 4] = w.pslot;
+    }
+  }
+  return DCP_OK;
+}
+
+extern "C" size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype) {
+  if (!plan || hq <= 0) return 0;
+  // the work lists are cached in the plan the first time a size or a launch asks for them
+  return bwd_workspace(const_cast<dcp_plan_t*>(plan), hq, hkv, d, dtype).total();
 }
 
 extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace,
@@ -190,16 +218,17 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
   if ((st = check_tensor("dv", t->dv, t->dv_stride_t, t->dv_stride_h, t->d)) != DCP_OK) return st;
   if (!t->lse) return fail(DCP_ERR_INVALID_ARG, "lse is NULL");
   if (plan->has_ranges && !t->attn_ranges) return fail(DCP_ERR_INVALID_ARG, "table has RANGES rows but attn_ranges is NULL");
-  const size_t need = dcp_bwd_workspace_bytes(plan, t->hq, t->hkv, t->d, t->dtype);
+  const BwdWorkspace wsz = bwd_workspace(plan, t->hq, t->hkv, t->d, t->dtype);
+  const size_t need = wsz.total();
   if (!workspace || workspace_bytes < need) return fail(DCP_ERR_WORKSPACE, "workspace is NULL or smaller than dcp_bwd_workspace_bytes");
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(DCP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
   hipStream_t s = (hipStream_t)stream;
   DevGroup gq, gkv;
   if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &gq)) != DCP_OK) return st;
-  if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv)) != DCP_OK) return st;
+  if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv, use_mfma ? t->hkv : 0)) != DCP_OK) return st;
   KTensors k = pack(plan, t);
-  size_t n_hT = (size_t)t->hq * (size_t)plan->q_rows * sizeof(float);
-  n_hT = (n_hT + 255) & ~(size_t)255;
+  const size_t n_hT = wsz.n_hT;
+  k.part = (float*)((char*)workspace + 2 * wsz.n_hT + wsz.n_bounds);
   float* delta = (float*)workspace;
   float* lse2 = (float*)((char*)workspace + n_hT);
   k.delta = delta;

@@ -6,6 +6,7 @@
 #include <map>
 #include <mutex>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "dcp.h"
@@ -22,11 +23,21 @@ dcp_status_t fail(dcp_status_t code, const std::string& msg);
       return ::dcp::fail(DCP_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e__));    \
   } while (0)
 
-// One (unit, tile) piece of work: `unit` indexes a Group's units, `tile` is the tile number
-// inside the unit's own block (tile * tile_rows is the first row).
+// One piece of work: `unit` indexes a Group's units, `tile` is the tile number inside the unit's own block
+// (tile * tile_rows is the first row), [e0, e1) the table rows of the unit this piece covers (all of them, unless
+// the work list was built with splitting).  `pslot` >= 0: the piece is one part of a split (unit, tile) and leaves
+// its fp32 result in that slot of the partial-sum workspace; -1: it writes the output itself.  32 bytes.
 struct WorkItem {
   int32_t unit;
   int32_t tile;
+  int32_t e0, e1;
+  int32_t pslot;
+  int32_t pad[3];
+};
+
+// A split (unit, tile): the parts' slots are first_pslot .. first_pslot + n_parts - 1, summed in that order.
+struct ReduceItem {
+  int32_t unit, tile, first_pslot, n_parts;
 };
 
 // Device view of a grouping of table rows by a unit (an output block / slot, or a KV block).
@@ -48,7 +59,9 @@ struct DevGroup {
   const int32_t* ent_t32;    // [nnz]     index of the other block's first 32-row tile (range-bound summaries)
   const int32_t* ent_rec;    // [nnz][8]  the same per row in one record: start, len, kind, moff, t32, 0, 0, 0 (32-byte aligned)
   const WorkItem* items;     // [n_items] longest first
+  const ReduceItem* reduce;  // [n_reduce] split (unit, tile)s, or null
   int32_t n_items;
+  int32_t n_reduce;
   int32_t n_units;
 };
 
@@ -56,9 +69,16 @@ struct HostGroup {
   std::vector<int32_t> unit_blk, unit_out, ptr, idx, ent_blk, ent_start, ent_len, ent_kind;
 };
 
+struct HostItems {
+  std::vector<WorkItem> items;
+  std::vector<ReduceItem> reduce;
+  int32_t n_pslots = 0;
+};
+
 struct DevItems {
   WorkItem* items = nullptr;
-  int32_t n_items = 0;
+  ReduceItem* reduce = nullptr;
+  int32_t n_items = 0, n_reduce = 0;
 };
 
 }  // namespace dcp
@@ -83,11 +103,16 @@ struct dcp_plan {
   int32_t* dev_arena = nullptr;
   dcp::DevGroup d_fwd{}, d_bwdq{}, d_bwdkv{};
   const int32_t *d_merge_ptr = nullptr, *d_merge_idx = nullptr, *d_slot_qblk = nullptr, *d_q_mem0 = nullptr, *d_blk_t32 = nullptr;
-  std::map<std::pair<int, int>, dcp::DevItems> items;  // (group id, tile rows) -> work list
+  // (group id, tile rows, split heads) -> work list; split heads = 0: no splitting, else the number of workgroups
+  // launched per item (the long items are cut so that no workgroup outlasts the rest of the grid by much)
+  typedef std::tuple<int, int, int> ItemKey;
+  std::map<ItemKey, dcp::HostItems> h_items;
+  std::map<ItemKey, dcp::DevItems> items;
 
   dcp_status_t ensure_device(hipStream_t stream);
-  // group id: 0 fwd, 1 bwdq, 2 bwdkv
-  dcp_status_t group_for(int group_id, int tile_rows, hipStream_t stream, dcp::DevGroup* out);
+  // group id: 0 fwd, 1 bwdq, 2 bwdkv.  Host only; takes the plan's lock.
+  const dcp::HostItems& host_items(int group_id, int tile_rows, int split_heads);
+  dcp_status_t group_for(int group_id, int tile_rows, hipStream_t stream, dcp::DevGroup* out, int split_heads = 0);
 };
 
 // Blockwise Copy list: validated entries cut into chunks of at most kCopyChunkRows rows.

@@ -12,6 +12,7 @@ struct KTensors {
   const float* delta;      // backward input [Hq,T]
   const float* lse2;       // backward input [Hq,T]: max(lse * log2(e), -FLT_MAX), made by the preprocess
   const int32_t* ranges;   // [T,4] or null
+  float* part;             // backward, or null: fp32 partial sums of split dK/dV items, [slot][KV head][dK, dV][128 keys][D]
   const int32_t* qbounds;  // backward, or null: [32-row tiles of all blocks + 1][8] bounds of the rows' ranges (RangeBounds order)
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh, dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
   int64_t q_rows;   // rows of the Q-type buffers (= packed tokens without block buffers): row pitch of lse / delta / lse2
@@ -42,6 +43,7 @@ bool mfma_supports(int32_t dtype, int32_t d);
 int mfma_fwd_tile();
 int mfma_dq_tile();
 int mfma_dkv_tile();
+size_t mfma_dkv_part_bytes(int32_t n_pslots, int32_t hkv);   // size of KTensors::part for that many slots
 dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s);

@@ -48,9 +48,10 @@ struct QIter {
   int moff;  // the Q block's rows sit at (packed index + moff) in the Q-type buffers
   int t32;   // index of the Q block's first 32-row tile in qbounds
   int qs;    // first query of the current tile
-  __device__ QIter(const DevGroup& g, int unit, int G_, const int32_t* qb)
+  // [e0, e1): the table rows of the unit this workgroup covers
+  __device__ QIter(const DevGroup& g, int e0, int e1, int G_, const int32_t* qb)
       : rec((const int4*)g.ent_rec), qbounds((const int4*)qb) {
-    e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; moff = 0; t32 = 0; qs = 0;
+    e = e0 - 1; e_end = e1; hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; moff = 0; t32 = 0; qs = 0;
   }
   // Which of the (at most 64) 64-query tiles of the current RANGES row may see a key of [k_lo, k_end): lane l merges
   // the bounds of the two 32-row halves of tile l.  Returns the ballot (wave-uniform).
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
   if (!decode_wg(g.n_items, t.hkv, 1, &item, &hk)) return;
   const int G = t.hq / t.hkv;
   WorkItem w = g.items[item];
-  w.unit = uni(w.unit); w.tile = uni(w.tile);
+  w.unit = uni(w.unit); w.tile = uni(w.tile); w.e0 = uni(w.e0); w.e1 = uni(w.e1); w.pslot = uni(w.pslot);
   const int kb = uni(g.unit_blk[w.unit]);
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
   }
   const float c_log2 = t.scale * kLog2e;
 
-  QIter<RANGES> it(g, w.unit, G, t.qbounds);
+  QIter<RANGES> it(g, w.e0, w.e1, G, t.qbounds);
   auto issue = [&](char* stage) {
     const int head = hk * G + it.hh;
     const int last = it.q1 - 1;
@@ -306,6 +307,20 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
     buf ^= kStageBytes;
   }
   if (!kvalid) return;
+  if (w.pslot >= 0) {
+    // one part of a split item: the fp32 sums go to the part's slot, the reduce kernel adds the parts up
+    float* pk = t.part + (((int64_t)w.pslot * t.hkv + hk) * 2 * TK + wrow0 + li) * 128 + 4 * lh;
+    float* pv = pk + TK * 128;
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int a = 0; a < 4; a++) {
+        *(float4*)(pk + 32 * dt + 8 * a) = make_float4(st.dk[dt][4 * a] * t.scale, st.dk[dt][4 * a + 1] * t.scale,
+                                                       st.dk[dt][4 * a + 2] * t.scale, st.dk[dt][4 * a + 3] * t.scale);
+        *(float4*)(pv + 32 * dt + 8 * a) = make_float4(st.dv[dt][4 * a], st.dv[dt][4 * a + 1], st.dv[dt][4 * a + 2], st.dv[dt][4 * a + 3]);
+      }
+    return;
+  }
   bf16_t* dkp = (bf16_t*)t.dk + (int64_t)(wk_lo + li + koff) * t.dk_st + (int64_t)hk * t.dk_sh;
   bf16_t* dvp = (bf16_t*)t.dv + (int64_t)(wk_lo + li + koff) * t.dv_st + (int64_t)hk * t.dv_sh;
 #pragma unroll
@@ -320,6 +335,37 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
       *(uint2*)(dkp + 32 * dt + 8 * a + 4 * lh) = pk;
       *(uint2*)(dvp + 32 * dt + 8 * a + 4 * lh) = pv;
     }
+}
+
+// Adds up the parts of every split (KV tile, KV head) in slot order (the same sum whatever ran first) and writes
+// the bf16 dK / dV rows.  One workgroup per (split item, KV head); thread x owns 8 floats of a 128-float row.
+__global__ __launch_bounds__(256) void dkv_reduce_kernel(DevGroup g, KTensors t) {
+  constexpr int TK = 128;
+  const ReduceItem r = g.reduce[blockIdx.x];
+  const int hk = blockIdx.y;
+  const int kb = g.unit_blk[r.unit];
+  const int n_rows = min(TK, g.blk_len[kb] - r.tile * TK);
+  const int64_t mem0 = (int64_t)g.blk_start[kb] + r.tile * TK + g.unit_moff[r.unit];
+  const int col = 8 * (threadIdx.x & 15);
+  for (int which = 0; which < 2; which++) {
+    bf16_t* dst = which ? (bf16_t*)t.dv : (bf16_t*)t.dk;
+    const int64_t st_t = which ? t.dv_st : t.dk_st, st_h = which ? t.dv_sh : t.dk_sh;
+    for (int row = threadIdx.x >> 4; row < n_rows; row += 16) {
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int p = 0; p < r.n_parts; p++) {
+        const float* src = t.part + ((((int64_t)(r.first_pslot + p) * t.hkv + hk) * 2 + which) * TK + row) * 128 + col;
+        const float4 a = *(const float4*)src, b = *(const float4*)(src + 4);
+        acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+        acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
+      }
+      uint4 o;
+      o.x = (uint32_t)f32_to_bf16(acc[0]) | ((uint32_t)f32_to_bf16(acc[1]) << 16);
+      o.y = (uint32_t)f32_to_bf16(acc[2]) | ((uint32_t)f32_to_bf16(acc[3]) << 16);
+      o.z = (uint32_t)f32_to_bf16(acc[4]) | ((uint32_t)f32_to_bf16(acc[5]) << 16);
+      o.w = (uint32_t)f32_to_bf16(acc[6]) | ((uint32_t)f32_to_bf16(acc[7]) << 16);
+      *(uint4*)(dst + (mem0 + row) * st_t + (int64_t)hk * st_h + col) = o;
+    }
+  }
 }
 
 dcp_status_t mfma_range_bounds(const int32_t* blk_start, const int32_t* blk_len, const int32_t* blk_t32, int32_t n_blocks,
@@ -339,7 +385,13 @@ dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (t.ranges) hipLaunchKernelGGL(mfma_dkv_kernel<true>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   else hipLaunchKernelGGL(mfma_dkv_kernel<false>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
+  if (g.n_reduce > 0) {
+    hipLaunchKernelGGL(dkv_reduce_kernel, dim3(g.n_reduce, t.hkv), dim3(256), 0, s, g, t);
+    DCP_HIP_TRY(hipGetLastError());
+  }
   return DCP_OK;
 }
+
+size_t mfma_dkv_part_bytes(int32_t n_pslots, int32_t hkv) { return (size_t)n_pslots * (size_t)hkv * 2 * 128 * 128 * sizeof(float); }
 
 }  // namespace dcp

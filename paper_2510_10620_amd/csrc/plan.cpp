@@ -330,6 +330,7 @@ extern "C" dcp_status_t dcp_plan_set_block_buffers(dcp_plan_t* plan, const int32
     }
   }
   plan->buffers = true;
+  plan->h_items.clear();   // work lists leave out absent blocks
   plan->q_slot.assign(q_slot, q_slot + plan->n_blocks);
   plan->kv_slot.assign(kv_slot, kv_slot + plan->n_blocks);
   for (int32_t b = 0; b < plan->n_blocks; b++) {
@@ -348,8 +349,10 @@ extern "C" dcp_status_t dcp_plan_destroy(dcp_plan_t* plan) {
     (void)hipGetDevice(&cur);
     if (plan->device >= 0 && cur != plan->device) (void)hipSetDevice(plan->device);
     if (plan->dev_arena) (void)hipFree(plan->dev_arena);
-    for (auto& kv : plan->items)
+    for (auto& kv : plan->items) {
       if (kv.second.items) (void)hipFree(kv.second.items);
+      if (kv.second.reduce) (void)hipFree(kv.second.reduce);
+    }
     if (plan->device >= 0 && cur >= 0 && cur != plan->device) (void)hipSetDevice(cur);
   }
   delete plan;
@@ -454,7 +457,9 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     ds[i]->blk_start = dev_arena + o_bs;
     ds[i]->blk_len = dev_arena + o_bl;
     ds[i]->items = nullptr;
+    ds[i]->reduce = nullptr;
     ds[i]->n_items = 0;
+    ds[i]->n_reduce = 0;
     ds[i]->n_units = (int32_t)gs[i]->unit_blk.size();
   }
   d_merge_ptr = dev_arena + o_mp;
@@ -480,49 +485,118 @@ static int64_t tile_cost(int32_t kind, int64_t r0, int64_t r1, int64_t c0, int64
   return (r1 - r0) * (c1 - c0) / 2;  // RANGES: unknown without the arrays; half is the estimate
 }
 
-dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, DevGroup* out) {
+// Workgroups the chip holds at once in the kernels that split their items (2 per CU, 256 CUs).
+static constexpr int64_t kResidentWorkgroups = 512;
+static constexpr int32_t kMaxParts = 64;
+
+const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
+  std::lock_guard<std::mutex> lock(mu);
+  const ItemKey key(gid, tile_rows, split_heads);
+  auto hit = h_items.find(key);
+  if (hit != h_items.end()) return hit->second;
+  HostGroup* hg = gid == 0 ? &fwd : (gid == 1 ? &bwdq : &bwdkv);
+  struct Scored { WorkItem w; int64_t cost; };
+  std::vector<Scored> sc;
+  std::vector<int64_t> ecost;   // per-entry costs of the item being built
+  // first pass: whole items and the total cost
+  int64_t total = 0;
+  for (int32_t u = 0; u < (int32_t)hg->unit_blk.size(); u++) {
+    int32_t b = hg->unit_blk[u];
+    if (b < 0) continue;  // unused slot
+    if (buffers && (gid == 2 ? kv_slot[b] : q_slot[b]) < 0) continue;  // block absent from its buffer: nothing to write
+    int32_t nt = (blk_len[b] + tile_rows - 1) / tile_rows;
+    for (int32_t t = 0; t < nt; t++) {
+      int64_t r0 = blk_start[b] + (int64_t)t * tile_rows;
+      int64_t r1 = std::min<int64_t>(r0 + tile_rows, blk_start[b] + blk_len[b]);
+      int64_t cost = 0;
+      for (int32_t e = hg->ptr[u]; e < hg->ptr[u + 1]; e++)
+        cost += tile_cost(hg->ent_kind[e], r0, r1, hg->ent_start[e], hg->ent_start[e] + hg->ent_len[e], gid == 2);
+      sc.push_back({{u, t, hg->ptr[u], hg->ptr[u + 1], -1, {0, 0, 0}}, cost});
+      total += cost;
+    }
+  }
+  HostItems hi;
+  if (split_heads > 0) {
+    // An item longer than a quarter of a resident workgroup's share of the whole launch is cut, along its table
+    // rows, into parts of about that length: the tail of the launch is then a fraction of its body whatever the
+    // longest item was (one key tile under a sink or one query tile that sees everything can otherwise outlast
+    // the rest of the grid).  Parts hold whole table rows, at most kMaxParts of them per item.
+    const int64_t limit = std::max<int64_t>(1, total * split_heads / kResidentWorkgroups / 4);
+    std::vector<Scored> cut;
+    for (const Scored& it : sc) {
+      const int32_t n_ent = it.w.e1 - it.w.e0;
+      int64_t want = (it.cost + limit - 1) / limit;
+      const int32_t n_parts = (int32_t)std::min<int64_t>(std::min<int64_t>(want, n_ent), kMaxParts);
+      if (n_parts <= 1) { cut.push_back(it); continue; }
+      const WorkItem& w = it.w;
+      int64_t r0 = blk_start[hg->unit_blk[w.unit]] + (int64_t)w.tile * tile_rows;
+      int64_t r1 = std::min<int64_t>(r0 + tile_rows, blk_start[hg->unit_blk[w.unit]] + blk_len[hg->unit_blk[w.unit]]);
+      ecost.assign(n_ent, 0);
+      for (int32_t e = w.e0; e < w.e1; e++)
+        ecost[e - w.e0] = tile_cost(hg->ent_kind[e], r0, r1, hg->ent_start[e], hg->ent_start[e] + hg->ent_len[e], gid == 2);
+      // contiguous chunks of table rows of about cost / n_parts each, every chunk non-empty
+      hi.reduce.push_back({w.unit, w.tile, hi.n_pslots, n_parts});
+      int32_t e = w.e0;
+      int64_t done = 0;
+      for (int32_t p = 0; p < n_parts; p++) {
+        const int32_t left_parts = n_parts - p - 1;
+        const int64_t goal = it.cost * (p + 1) / n_parts;
+        int32_t e_hi = e + 1;
+        int64_t c = ecost[e - w.e0];
+        while (e_hi < w.e1 - left_parts && done + c < goal) { c += ecost[e_hi - w.e0]; e_hi++; }
+        if (p == n_parts - 1) { while (e_hi < w.e1) { c += ecost[e_hi - w.e0]; e_hi++; } }
+        cut.push_back({{w.unit, w.tile, e, e_hi, hi.n_pslots + p, {0, 0, 0}}, c});
+        done += c;
+        e = e_hi;
+      }
+      hi.n_pslots += n_parts;
+    }
+    sc.swap(cut);
+  }
+  std::stable_sort(sc.begin(), sc.end(), [](const Scored& a, const Scored& b) { return a.cost > b.cost; });
+  hi.items.resize(sc.size());
+  for (size_t i = 0; i < sc.size(); i++) hi.items[i] = sc[i].w;
+  return h_items.emplace(key, std::move(hi)).first->second;
+}
+
+template <class T>
+static dcp_status_t upload(const std::vector<T>& v, T** dev, hipStream_t stream) {
+  *dev = nullptr;
+  if (v.empty()) return DCP_OK;
+  DCP_HIP_TRY(hipMalloc((void**)dev, v.size() * sizeof(T)));
+  hipError_t e = hipMemcpyAsync(*dev, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) {
+    (void)hipFree(*dev);
+    *dev = nullptr;
+    return fail(DCP_ERR_HIP, std::string("work list upload: ") + hipGetErrorString(e));
+  }
+  return DCP_OK;
+}
+
+dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, DevGroup* out, int split_heads) {
   dcp_status_t st = ensure_device(stream);
   if (st != DCP_OK) return st;
+  const HostItems& hi = host_items(gid, tile_rows, split_heads);
   std::lock_guard<std::mutex> lock(mu);
-  HostGroup* hg = gid == 0 ? &fwd : (gid == 1 ? &bwdq : &bwdkv);
   DevGroup dg = gid == 0 ? d_fwd : (gid == 1 ? d_bwdq : d_bwdkv);
-  auto key = std::make_pair(gid, tile_rows);
+  const ItemKey key(gid, tile_rows, split_heads);
   auto it = items.find(key);
   if (it == items.end()) {
-    struct Scored { WorkItem w; int64_t cost; };
-    std::vector<Scored> sc;
-    for (int32_t u = 0; u < (int32_t)hg->unit_blk.size(); u++) {
-      int32_t b = hg->unit_blk[u];
-      if (b < 0) continue;  // unused slot
-      if (buffers && (gid == 2 ? kv_slot[b] : q_slot[b]) < 0) continue;  // block absent from its buffer: nothing to write
-      int32_t nt = (blk_len[b] + tile_rows - 1) / tile_rows;
-      for (int32_t t = 0; t < nt; t++) {
-        int64_t r0 = blk_start[b] + (int64_t)t * tile_rows;
-        int64_t r1 = std::min<int64_t>(r0 + tile_rows, blk_start[b] + blk_len[b]);
-        int64_t cost = 0;
-        for (int32_t e = hg->ptr[u]; e < hg->ptr[u + 1]; e++)
-          cost += tile_cost(hg->ent_kind[e], r0, r1, hg->ent_start[e], hg->ent_start[e] + hg->ent_len[e], gid == 2);
-        sc.push_back({{u, t}, cost});
-      }
-    }
-    std::stable_sort(sc.begin(), sc.end(), [](const Scored& a, const Scored& b) { return a.cost > b.cost; });
-    std::vector<WorkItem> w(sc.size());
-    for (size_t i = 0; i < sc.size(); i++) w[i] = sc[i].w;
     DevItems di;
-    di.n_items = (int32_t)w.size();
-    if (!w.empty()) {
-      DCP_HIP_TRY(hipMalloc((void**)&di.items, w.size() * sizeof(WorkItem)));
-      hipError_t e = hipMemcpyAsync(di.items, w.data(), w.size() * sizeof(WorkItem), hipMemcpyHostToDevice, stream);
-      if (e == hipSuccess) e = hipStreamSynchronize(stream);
-      if (e != hipSuccess) {
-        (void)hipFree(di.items);
-        return fail(DCP_ERR_HIP, std::string("work list upload: ") + hipGetErrorString(e));
-      }
+    di.n_items = (int32_t)hi.items.size();
+    di.n_reduce = (int32_t)hi.reduce.size();
+    if ((st = upload(hi.items, &di.items, stream)) != DCP_OK) return st;
+    if ((st = upload(hi.reduce, &di.reduce, stream)) != DCP_OK) {
+      if (di.items) (void)hipFree(di.items);
+      return st;
     }
     it = items.emplace(key, di).first;
   }
   dg.items = it->second.items;
   dg.n_items = it->second.n_items;
+  dg.reduce = it->second.reduce;
+  dg.n_reduce = it->second.n_reduce;
   *out = dg;
   return DCP_OK;
 }

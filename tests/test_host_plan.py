@@ -111,6 +111,51 @@ def test_plan_groupings_bit_exact_vs_oracle():
     assert np.array_equal(plan2.export("BWDKV_IDX"), idx)
 
 
+@pytest.mark.parametrize("spec,lens,B,hkv", [
+    (W.MaskSpec("causal"), [5000, 300, 1200], 256, 2),                       # a long sequence: early key tiles see far more
+    (W.MaskSpec("causal_blockwise", window=2, sink=1, mblock=64), [4096, 700], 128, 4),   # sink keys seen by every query
+    (W.MaskSpec("causal"), [100], 128, 1),                                     # one block, one table row: nothing to cut
+])
+def test_dkv_work_list_is_an_exact_partition(spec, lens, B, hkv):
+    """Every (kv_blk, 128-key tile) appears either once, whole, with pslot -1, or as parts whose table-row ranges
+    tile the block's CSR range in order without gap or overlap, with consecutive slots nobody else uses."""
+    cu = W.cu_from_lengths(lens)
+    table = _oracle_table(spec, cu, B)
+    plan = P.dcp_plan_create(cu, B, table)
+    items = P.dcp_plan_export_dkv_items(plan, hkv)
+    ptr = plan.export("BWDKV_PTR")
+    blk_len = plan.export("BLK_LEN")
+    by_tile = {}
+    for u, t, e0, e1, ps in items.tolist():
+        by_tile.setdefault((u, t), []).append((e0, e1, ps))
+    want = {(u, t) for u in range(len(blk_len)) if ptr[u + 1] > ptr[u] for t in range((blk_len[u] + 127) // 128)}
+    assert set(by_tile) == want
+    slots = []
+    n_split = 0
+    for (u, t), parts in by_tile.items():
+        parts.sort()
+        assert parts[0][0] == ptr[u] and parts[-1][1] == ptr[u + 1]
+        for (a0, a1, _), (b0, b1, _) in zip(parts, parts[1:]):
+            assert a1 == b0
+        assert all(e1 > e0 for e0, e1, _ in parts)
+        if len(parts) == 1:
+            assert parts[0][2] == -1
+        else:
+            n_split += 1
+            ps = [p for _, _, p in parts]
+            assert ps == list(range(ps[0], ps[0] + len(ps)))     # table-row order = slot order = summation order
+            slots += ps
+    assert sorted(slots) == list(range(len(slots)))
+    if len(lens) > 1:
+        assert n_split > 0            # the long items of these workloads are cut
+    else:
+        assert n_split == 0
+    # the workspace grows by the partial sums: 2 x 128 x 128 fp32 per slot and KV head
+    base = P.dcp_bwd_workspace_bytes(plan, 4 * hkv, hkv, 64, P.DCP_BF16)       # D = 64: scalar kernels, no partial sums
+    full = P.dcp_bwd_workspace_bytes(plan, 4 * hkv, hkv, 128, P.DCP_BF16)
+    assert full - base == len(slots) * hkv * 2 * 128 * 128 * 4
+
+
 def _status(fn, *a, **k):
     with pytest.raises(P.DcpError) as ei:
         fn(*a, **k)
