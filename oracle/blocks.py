@@ -8,7 +8,7 @@ global block id = blocks of earlier sequences + index within the sequence.
 """
 import numpy as np
 
-MASK_NONE, MASK_CAUSAL, MASK_RANGES, MASK_SKIP = 0, 1, 2, 3
+MASK_NONE, MASK_CAUSAL, MASK_RANGES, MASK_SKIP, MASK_WINDOW = 0, 1, 2, 3, 4
 
 
 def block_partition(cu_seqlens, B):
@@ -29,12 +29,13 @@ def block_partition(cu_seqlens, B):
                 blk_start=np.asarray(blk_start, np.int64), blk_end=np.asarray(blk_end, np.int64))
 
 
-def table_from_mask(mask_rows, cu_seqlens, B):
+def table_from_mask(mask_rows, cu_seqlens, B, other_kind=MASK_RANGES):
     """Block generation (Sec. 4.1): a computation block (Q_i, KV_j) exists iff the mask tile
     M[rows of Q_i, cols of KV_j] is not all zeros.  `mask_rows(s, L, r0, r1)` returns the dense
     bool rows of sequence s.  Classification of a tile: all ones -> NONE; equal to the causal
-    predicate (col <= row) on the tile -> CAUSAL; otherwise RANGES.  Rows are emitted in
-    ascending (q_blk, kv_blk) order.  int32[n, 3]."""
+    predicate (col <= row) on the tile -> CAUSAL; otherwise `other_kind`: RANGES (the per-token
+    range arrays describe the tile) or, for a table made from a window / sink specification,
+    WINDOW.  Rows are emitted in ascending (q_blk, kv_blk) order.  int32[n, 3]."""
     cu = np.asarray(cu_seqlens, dtype=np.int64)
     part = block_partition(cu, B)
     rows = []
@@ -56,7 +57,7 @@ def table_from_mask(mask_rows, cu_seqlens, B):
                 elif np.array_equal(tile, np.arange(c0, c1)[None, :] <= ii):
                     kind = MASK_CAUSAL
                 else:
-                    kind = MASK_RANGES
+                    kind = other_kind
                 rows.append((g0 + i, g0 + j, kind))
     return np.asarray(rows, dtype=np.int32).reshape(-1, 3)
 
@@ -74,9 +75,12 @@ class Visibility:
     """The mask a block table *defines*: key j is visible to query i iff some listed entry
     (q_blk, kv_blk, kind) covers (i, j) and its predicate holds:
       NONE always; CAUSAL j <= i; RANGES packed index of j in [r0,r1) or [r2,r3) of row i;
+      WINDOW (sliding window with attention sink, Sec. 2.4 "Lambda"; parameters window W and
+      sink, one pair for the whole table) j <= i and (i - j < W or j is one of the first `sink`
+      tokens of the sequence);
       SKIP never.  Unlisted pairs are invisible."""
 
-    def __init__(self, cu_seqlens, B, table, ranges=None, select=None):
+    def __init__(self, cu_seqlens, B, table, ranges=None, select=None, window=None):
         self.cu = np.asarray(cu_seqlens, dtype=np.int64)
         self.B = int(B)
         self.part = block_partition(self.cu, B)
@@ -85,6 +89,7 @@ class Visibility:
             t = t[np.asarray(select)]
         self.table = t
         self.ranges = None if ranges is None else np.asarray(ranges, dtype=np.int64)
+        self.window = None if window is None else (int(window[0]), int(window[1]))   # (W, sink)
         self.by_q = {}
         for e in range(len(t)):
             self.by_q.setdefault(int(t[e, 0]), []).append(e)
@@ -117,6 +122,9 @@ class Visibility:
                     r = self.ranges[base + a0: base + a1]
                     vis = ((j_pack >= r[:, 0:1]) & (j_pack < r[:, 1:2])) | \
                           ((j_pack >= r[:, 2:3]) & (j_pack < r[:, 3:4]))
+                elif kind == MASK_WINDOW:
+                    W, sink = self.window
+                    vis = (j_pack <= i_pack) & ((i_pack - j_pack < W) | (j_pack - base < sink))
                 else:
                     raise ValueError(f"bad mask kind {kind}")
                 M[a0 - r0: a1 - r0, c0 - base: c1 - base] |= vis
@@ -137,6 +145,14 @@ class Visibility:
                 out[e] = (q1 - q0) * (c1 - c0)
             elif kind == MASK_CAUSAL:
                 out[e] = int(np.clip(i + 1 - c0, 0, c1 - c0).sum())
+            elif kind == MASK_WINDOW:
+                W, sink = self.window
+                base = int(self.cu[int(p["blk_seq"][qb])])
+                n = 0
+                for q in range(q0, q1):                      # plain count, key by key
+                    for k in range(c0, c1):
+                        n += int(k <= q and (q - k < W or k - base < sink))
+                out[e] = n
             else:
                 r = self.ranges[q0:q1]
                 j = np.arange(c0, c1, dtype=np.int64)[None, :]

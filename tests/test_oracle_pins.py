@@ -343,6 +343,37 @@ def test_table_defined_mask_equals_formula_mask(spec):
     assert (vis.pair_counts() > 0).all()
 
 
+@pytest.mark.parametrize("W_,sink", [(50, 0), (40, 7), (16, 16), (1, 0), (300, 3), (5, 400)])
+def test_window_kind_table_equals_formula_mask(W_, sink):
+    """A table whose edge tiles carry the WINDOW kind, with (window, sink) as its only parameters, defines the
+    sliding-window / lambda mask of Sec. 2.4: checked against the formula-side masks, which know nothing of
+    tables, and against the RANGES route on the same specification."""
+    rng = np.random.default_rng(23)
+    lens = [int(x) for x in rng.integers(20, 200, size=4)] + [1, 16]
+    B = 16
+    cu = W.cu_from_lengths(lens)
+    spec = W.MaskSpec("lambda", window=W_, sink=sink) if sink else W.MaskSpec("window", window=W_)
+    table = Bk.table_from_mask(mask_rows_fn(spec), cu, B, other_kind=Bk.MASK_WINDOW)
+    assert not (table[:, 2] == Bk.MASK_RANGES).any()
+    vis = Bk.Visibility(cu, B, table, window=(W_, sink))
+    total = 0
+    for s, L in enumerate(lens):
+        M = Mk.lambda_mask(L, W_, sink) if sink else Mk.window(L, W_)
+        assert np.array_equal(vis.rows(s, 0, L), M)
+        total += int(M.sum())
+    counts = vis.pair_counts()
+    assert int(counts.sum()) == total and (counts > 0).all()
+    # same rows, same counts as the RANGES route
+    t2 = Bk.table_from_mask(mask_rows_fn(spec), cu, B)
+    assert np.array_equal(table[:, :2], t2[:, :2])
+    assert np.array_equal(np.where(table[:, 2] == Bk.MASK_WINDOW, Bk.MASK_RANGES, table[:, 2]), t2[:, 2])
+    assert np.array_equal(Bk.Visibility(cu, B, t2, W.attn_ranges(spec, cu)).pair_counts(), counts)
+    # hand case: 6 tokens, window 3, sink 1 -> row 5 sees keys {0, 3, 4, 5}
+    v = Bk.Visibility([0, 6], 2, Bk.table_from_mask(mask_rows_fn(W.MaskSpec("lambda", window=3, sink=1)), [0, 6], 2,
+                                                    other_kind=Bk.MASK_WINDOW), window=(3, 1))
+    assert v.rows(0, 5, 6)[0].tolist() == [True, False, False, True, True, True]
+
+
 def test_block_partition_ragged():
     cu = W.cu_from_lengths([5, 8, 1])
     p = Bk.block_partition(cu, 4)
