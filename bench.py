@@ -334,16 +334,26 @@ def masks_section(torch, P, W, np, steps):
     """The same step (forward + backward) on the other mask families of the paper at their full shapes: sliding
     window (config 3), lambda (4), causal blockwise (6), shared question (7).  Not the headline metric."""
     res = {}
-    for cfg in (3, 4, 6, 7):
+    # (config, through WINDOW rows): the window / lambda masks are also timed with the WINDOW mask kind, which
+    # takes the window and sink sizes instead of the [T, 4] range array
+    for cfg, window_kind in ((3, False), (3, True), (4, False), (4, True), (6, False), (7, False)):
         w = W.make_workload(cfg)
-        table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
-        pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, table, w.ranges).sum())
+        if window_kind:
+            table = P.dcp_build_block_table_window(w.cu_seqlens, w.block_size, w.mask.window, w.mask.sink)
+            pairs = int(P.dcp_count_pairs_window(w.cu_seqlens, w.block_size, table, w.mask.window, w.mask.sink).sum())
+        else:
+            table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+            pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, table, w.ranges).sum())
         q, k, v, do = gen_tensors(torch, w, w.tensor_seed)
         plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)
         out = torch.empty_like(q)
         lse = torch.empty((w.hq, w.total_tokens), dtype=torch.float32, device="cuda")
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-        rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+        rg = None
+        if window_kind:
+            P.dcp_plan_set_window(plan, w.mask.window, w.mask.sink)
+        else:
+            rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
         ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plan, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
 
         def step():
@@ -359,8 +369,9 @@ def masks_section(torch, P, W, np, steps):
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
-        kinds = np.bincount(table[:, 2], minlength=3)
-        res[w.name] = dict(tokens=int(w.total_tokens), table_rows=int(len(table)), rows_none_causal_ranges=[int(x) for x in kinds[:3]],
+        kinds = np.bincount(np.where(table[:, 2] == P.DCP_MASK_WINDOW, P.DCP_MASK_RANGES, table[:, 2]), minlength=3)
+        res[w.name + ("_window_kind" if window_kind else "")] = dict(
+                           tokens=int(w.total_tokens), table_rows=int(len(table)), rows_none_causal_ranges=[int(x) for x in kinds[:3]],
                            visible_pairs=pairs, ms_per_step=round(ms, 3),
                            tflops=round(14 * pairs * w.hq * w.d / (ms * 1e-3) / 1e12, 1))
         del q, k, v, do, out, lse, dq, dk, dv, ws, plan

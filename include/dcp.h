@@ -38,7 +38,8 @@ typedef enum {
   DCP_ERR_INVALID_ARG = -1,    /* NULL pointer, negative size, bad stride, missing ranges ...   */
   DCP_ERR_BAD_CU_SEQLENS = -2, /* cu_seqlens[0] != 0 or not strictly increasing                 */
   DCP_ERR_BAD_TABLE = -3,      /* block id out of range, blocks of two sequences, duplicate row, */
-                               /* bad mask_kind, inconsistent output slot                        */
+                               /* bad mask_kind, RANGES and WINDOW rows together, inconsistent   */
+                               /* output slot                                                    */
   DCP_ERR_UNSUPPORTED = -4,    /* head_dim / dtype / head ratio no kernel covers                 */
   DCP_ERR_WORKSPACE = -5,      /* workspace NULL or too small                                    */
   DCP_ERR_HIP = -6             /* a HIP runtime call failed (message holds hipGetErrorString)    */
@@ -51,8 +52,15 @@ typedef enum {
  *          paper's "arrays specifying the index ranges each token should attend to, at most two
  *          ranges per token" (Sec. 5, Blockwise Attention); r is int32 [T, 4], packed-token
  *          coordinates, half open, an empty range has hi <= lo;
- *   SKIP   never (the row is ignored).                                                         */
-typedef enum { DCP_MASK_NONE = 0, DCP_MASK_CAUSAL = 1, DCP_MASK_RANGES = 2, DCP_MASK_SKIP = 3 } dcp_mask_kind_t;
+ *   SKIP   never (the row is ignored);
+ *   WINDOW sliding window with an attention sink (the lambda-shaped mask of Sec. 2.4; sink 0 gives
+ *          the plain sliding window): visible iff j <= i and (i - j < window or j is one of the
+ *          first `sink` tokens of the sequence).  window and sink are two numbers for the whole
+ *          plan (dcp_plan_set_window); no range array is read.  A table holds RANGES rows or
+ *          WINDOW rows, not both.                                                                */
+typedef enum {
+  DCP_MASK_NONE = 0, DCP_MASK_CAUSAL = 1, DCP_MASK_RANGES = 2, DCP_MASK_SKIP = 3, DCP_MASK_WINDOW = 4
+} dcp_mask_kind_t;
 
 typedef enum { DCP_BF16 = 0, DCP_F32 = 1 } dcp_dtype_t;
 
@@ -75,12 +83,24 @@ dcp_status_t dcp_build_block_table(const int32_t* cu_seqlens_host, int32_t n_seq
                                    const int32_t* attn_ranges_host, int32_t* table_out,
                                    int64_t capacity, int64_t* n_entries_out);
 
+/* The same block generation for a sliding window of `window` keys (the query included) with `sink`
+ * sink tokens per sequence, without range arrays: tiles that are neither all ones nor the causal
+ * predicate are tagged WINDOW.  window >= 1, sink >= 0.  Other arguments and errors as above. */
+dcp_status_t dcp_build_block_table_window(const int32_t* cu_seqlens_host, int32_t n_seq, int32_t block_size,
+                                          int32_t window, int32_t sink, int32_t* table_out, int64_t capacity,
+                                          int64_t* n_entries_out);
+
 /* Visible (query, key) pairs of every table row taken alone (the unit of the paper's FLOP
  * accounting for a computation block, Sec. 4.2 vertex weights).  attn_ranges_host may be NULL if
  * no row is RANGES.  pairs_out: host int64[n_entries].  Host only. */
 dcp_status_t dcp_count_pairs(const int32_t* cu_seqlens_host, int32_t n_seq, int32_t block_size,
                              const int32_t* table_host, int64_t n_entries,
                              const int32_t* attn_ranges_host, int64_t* pairs_out);
+
+/* dcp_count_pairs for tables with WINDOW rows (a RANGES row is DCP_ERR_BAD_TABLE here). */
+dcp_status_t dcp_count_pairs_window(const int32_t* cu_seqlens_host, int32_t n_seq, int32_t block_size,
+                                    const int32_t* table_host, int64_t n_entries, int32_t window, int32_t sink,
+                                    int64_t* pairs_out);
 
 /* Block buffers (Sec. 5 "Block buffers", and "Blockwise Attention": input and output blocks are
  * given by the buffer's start address and per-block offsets recorded with the block table, as in
@@ -114,6 +134,11 @@ dcp_status_t dcp_plan_create(dcp_plan_t** plan, const int32_t* cu_seqlens_host, 
                              int32_t block_size, const int32_t* table_host, int64_t n_entries,
                              const int32_t* out_slot_host, int32_t n_slots);
 dcp_status_t dcp_plan_destroy(dcp_plan_t* plan);
+
+/* Parameters of the plan's WINDOW rows: window >= 1 keys including the query, sink >= 0 tokens at the
+ * start of every sequence (both at most 2^30).  Launches of a plan with WINDOW rows fail with
+ * DCP_ERR_INVALID_ARG until this has been called; it may be called again between launches. */
+dcp_status_t dcp_plan_set_window(dcp_plan_t* plan, int32_t window, int32_t sink);
 
 typedef enum {
   DCP_EXPORT_BLK_START = 0, /* [n_blocks] packed token index of each block's first token        */
@@ -191,7 +216,7 @@ dcp_status_t dcp_merge_partials(dcp_plan_t* plan, const void* o_part, const floa
 dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_tokens, float* delta, void* stream);
 
 /* Bytes of device workspace dcp_block_attn_bwd needs for this plan and shape: delta and the rescaled LSE, each
- * float [Hq, rows of the Q-type buffers], plus, for tables with RANGES rows, 32 bytes per 32-row tile of every block
+ * float [Hq, rows of the Q-type buffers], plus, for tables with RANGES or WINDOW rows, 32 bytes per 32-row tile of every block
  * (bounds of the rows' range arrays, which let the dK/dV kernel pass over query tiles that see none of its keys),
  * plus, for the bf16 MFMA kernels, 128 KiB per KV head for every part of a split dK/dV item (fp32 partial sums, see
  * dcp_plan_export_dkv_items).  The first call for a given hkv builds and caches the work list in the plan. */

@@ -49,6 +49,11 @@ class Instr(ctypes.Structure):
 _SIGS = {
     "dcp_build_block_table": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, i32p, ctypes.c_int64, i64p]),
     "dcp_count_pairs": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, i64p]),
+    "dcp_build_block_table_window": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, i32p,
+                                                    ctypes.c_int64, i64p]),
+    "dcp_count_pairs_window": (ctypes.c_int, [i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int32,
+                                              ctypes.c_int32, i64p]),
+    "dcp_plan_set_window": (ctypes.c_int, [vp, ctypes.c_int32, ctypes.c_int32]),
     "dcp_program_create": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.POINTER(Instr), ctypes.c_int64]),
     "dcp_program_destroy": (ctypes.c_int, [vp]),
     "dcp_program_run": (ctypes.c_int, [vp, vp, vp]),

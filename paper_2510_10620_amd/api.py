@@ -11,7 +11,7 @@ from ._lib import Tensors
 DCP_OK = 0
 DCP_ERR_INVALID_ARG, DCP_ERR_BAD_CU_SEQLENS, DCP_ERR_BAD_TABLE = -1, -2, -3
 DCP_ERR_UNSUPPORTED, DCP_ERR_WORKSPACE, DCP_ERR_HIP = -4, -5, -6
-DCP_MASK_NONE, DCP_MASK_CAUSAL, DCP_MASK_RANGES, DCP_MASK_SKIP = 0, 1, 2, 3
+DCP_MASK_NONE, DCP_MASK_CAUSAL, DCP_MASK_RANGES, DCP_MASK_SKIP, DCP_MASK_WINDOW = 0, 1, 2, 3, 4
 DCP_BF16, DCP_F32 = 0, 1
 DCP_IMPL_AUTO, DCP_IMPL_SCALAR, DCP_IMPL_MFMA = 0, 1, 2
 EXPORTS = dict(BLK_START=0, BLK_LEN=1, BLK_SEQ=2, FWD_PTR=3, FWD_IDX=4, BWDQ_PTR=5, BWDQ_IDX=6,
@@ -54,6 +54,31 @@ def dcp_build_block_table(cu_seqlens, block_size, attn_ranges):
     table = np.zeros((n.value, 3), dtype=np.int32)
     _check(lib.dcp_build_block_table(cu_p, len(cu) - 1, block_size, rg_p, table.ctypes.data_as(_lib.i32p), n.value, ctypes.byref(n)))
     return table
+
+
+def dcp_build_block_table_window(cu_seqlens, block_size, window, sink=0):
+    """-> int32[n, 3] table for a sliding window of `window` keys with `sink` sink tokens; edge tiles are WINDOW rows."""
+    lib = _lib.load()
+    cu, cu_p = _i32(cu_seqlens)
+    n = ctypes.c_int64(0)
+    _check(lib.dcp_build_block_table_window(cu_p, len(cu) - 1, block_size, window, sink, None, 0, ctypes.byref(n)))
+    table = np.zeros((n.value, 3), dtype=np.int32)
+    _check(lib.dcp_build_block_table_window(cu_p, len(cu) - 1, block_size, window, sink, table.ctypes.data_as(_lib.i32p),
+                                            n.value, ctypes.byref(n)))
+    return table
+
+
+def dcp_count_pairs_window(cu_seqlens, block_size, table, window, sink=0):
+    lib = _lib.load()
+    cu, cu_p = _i32(cu_seqlens)
+    tb, tb_p = _i32(np.asarray(table).reshape(-1, 3))
+    out = np.zeros(len(tb), dtype=np.int64)
+    _check(lib.dcp_count_pairs_window(cu_p, len(cu) - 1, block_size, tb_p, len(tb), window, sink, out.ctypes.data_as(_lib.i64p)))
+    return out
+
+
+def dcp_plan_set_window(plan, window, sink=0):
+    _check(_lib.load().dcp_plan_set_window(plan.handle, int(window), int(sink)))
 
 
 def dcp_count_pairs(cu_seqlens, block_size, table, attn_ranges=None):

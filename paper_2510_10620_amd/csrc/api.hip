@@ -91,7 +91,10 @@ static KTensors pack(const dcp_plan_t* plan, const dcp_tensors_t* t) {
   k.q = t->q; k.k = t->k; k.v = t->v; k.dout = t->dout; k.out_in = t->out;
   k.out = t->out; k.dq = t->dq; k.dk = t->dk; k.dv = t->dv;
   k.lse = t->lse; k.delta = nullptr;
-  k.ranges = plan->has_ranges ? t->attn_ranges : nullptr;   // kernels skip all range work when no row is RANGES
+  k.ranges = plan->has_ranges ? t->attn_ranges : nullptr;   // kernels skip all range work when no row has per-token ranges
+  k.window = plan->has_window ? plan->window : 0;
+  k.sink = plan->has_window ? plan->sink : 0;
+  k.masked = (plan->has_ranges || plan->has_window) ? 1 : 0;
   k.qbounds = nullptr;
   k.q_st = t->q_stride_t; k.q_sh = t->q_stride_h; k.k_st = t->k_stride_t; k.k_sh = t->k_stride_h;
   k.v_st = t->v_stride_t; k.v_sh = t->v_stride_h; k.o_st = t->o_stride_t; k.o_sh = t->o_stride_h;
@@ -118,6 +121,7 @@ extern "C" dcp_status_t dcp_block_attn_fwd(dcp_plan_t* plan, const dcp_tensors_t
   if (!t->lse) return fail(DCP_ERR_INVALID_ARG, "lse is NULL");
   if (!plan->use_slots && (st = check_tensor("out", t->out, t->o_stride_t, t->o_stride_h, t->d)) != DCP_OK) return st;
   if (plan->has_ranges && !t->attn_ranges) return fail(DCP_ERR_INVALID_ARG, "table has RANGES rows but attn_ranges is NULL");
+  if (plan->has_window && plan->window <= 0) return fail(DCP_ERR_INVALID_ARG, "table has WINDOW rows but dcp_plan_set_window was not called");
   hipStream_t s = (hipStream_t)stream;
   DevGroup g;
   if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g)) != DCP_OK) return st;
@@ -171,8 +175,8 @@ static BwdWorkspace bwd_workspace(dcp_plan_t* plan, int32_t hq, int32_t hkv, int
   BwdWorkspace w{};
   w.n_hT = (size_t)hq * (size_t)plan->q_rows * sizeof(float);
   w.n_hT = (w.n_hT + 255) & ~(size_t)255;
-  // range-bound summaries of every 32-row tile (+1 spare entry), only for tables with RANGES rows
-  w.n_bounds = plan->has_ranges ? ((size_t)plan->blk_t32.back() + 1) * 8 * sizeof(int32_t) : 0;
+  // range-bound summaries of every 32-row tile (+1 spare entry), only for tables with RANGES or WINDOW rows
+  w.n_bounds = (plan->has_ranges || plan->has_window) ? ((size_t)plan->blk_t32.back() + 1) * 8 * sizeof(int32_t) : 0;
   w.n_bounds = (w.n_bounds + 255) & ~(size_t)255;
   if (hkv > 0 && mfma_supports(dtype, d)) w.n_part = mfma_dkv_part_bytes(plan->host_items(2, mfma_dkv_tile(), hkv).n_pslots, hkv);
   return w;
@@ -218,6 +222,7 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
   if ((st = check_tensor("dv", t->dv, t->dv_stride_t, t->dv_stride_h, t->d)) != DCP_OK) return st;
   if (!t->lse) return fail(DCP_ERR_INVALID_ARG, "lse is NULL");
   if (plan->has_ranges && !t->attn_ranges) return fail(DCP_ERR_INVALID_ARG, "table has RANGES rows but attn_ranges is NULL");
+  if (plan->has_window && plan->window <= 0) return fail(DCP_ERR_INVALID_ARG, "table has WINDOW rows but dcp_plan_set_window was not called");
   const BwdWorkspace wsz = bwd_workspace(plan, t->hq, t->hkv, t->d, t->dtype);
   const size_t need = wsz.total();
   if (!workspace || workspace_bytes < need) return fail(DCP_ERR_WORKSPACE, "workspace is NULL or smaller than dcp_bwd_workspace_bytes");
@@ -233,11 +238,10 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
   float* lse2 = (float*)((char*)workspace + n_hT);
   k.delta = delta;
   k.lse2 = lse2;
-  if (plan->has_ranges && use_mfma) {
+  if (k.masked && use_mfma) {
     int32_t* qb = (int32_t*)((char*)workspace + 2 * n_hT);
     k.qbounds = qb;
-    if ((st = mfma_range_bounds(gkv.blk_start, gkv.blk_len, plan->d_blk_t32, plan->n_blocks, plan->block_size, t->attn_ranges, qb, s)) != DCP_OK)
-      return st;
+    if ((st = mfma_range_bounds(gkv, k, plan->d_blk_t32, plan->n_blocks, qb, s)) != DCP_OK) return st;
   }
   {
     ProfScope ps(DCP_K_DELTA, s);

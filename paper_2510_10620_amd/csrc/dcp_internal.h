@@ -49,9 +49,10 @@ struct DevGroup {
   const int32_t* ptr;        // [n_units + 1]
   const int32_t* ent_start;  // [nnz]
   const int32_t* ent_len;    // [nnz]
-  const int32_t* ent_kind;   // [nnz]
+  const int32_t* ent_kind;   // [nnz]     0 NONE, 1 CAUSAL, 2 per-row ranges (RANGES, and WINDOW rows: their ranges are worked out)
   const int32_t* blk_start;  // [n_blocks]
   const int32_t* blk_len;    // [n_blocks]
+  const int32_t* blk_s0;     // [n_blocks] first packed token of the block's sequence
   // Block buffers (Sec. 5): a token's row in memory is its packed index plus the offset of its block,
   // slot * block_size - blk_start (0 for packed tensors).
   const int32_t* unit_moff;  // [n_units] offset of the unit's own block (Q side for fwd / dQ, KV side for dK/dV)
@@ -86,7 +87,8 @@ struct DevItems {
 struct dcp_plan {
   int32_t n_seq = 0, block_size = 0, n_blocks = 0, n_slots = 0;
   int64_t total_tokens = 0, n_kept = 0;
-  bool use_slots = false, has_ranges = false;
+  bool use_slots = false, has_ranges = false, has_window = false;
+  int32_t window = 0, sink = 0;   // parameters of the WINDOW rows (window 0: not set)
   // block buffers: slot of every block in the Q-type and the KV-type buffer (-1: absent), rows per buffer
   bool buffers = false;
   std::vector<int32_t> q_slot, kv_slot, q_moff, kv_moff;

@@ -11,7 +11,9 @@ struct KTensors {
   float* lse;              // forward: output; backward: input
   const float* delta;      // backward input [Hq,T]
   const float* lse2;       // backward input [Hq,T]: max(lse * log2(e), -FLT_MAX), made by the preprocess
-  const int32_t* ranges;   // [T,4] or null
+  const int32_t* ranges;   // [T,4] or null (tables without RANGES rows)
+  int32_t window, sink;    // window > 0: the table has WINDOW rows; their per-token ranges are worked out, not read
+  int32_t masked;          // the table has RANGES or WINDOW rows (rows with per-token ranges)
   float* part;             // backward, or null: fp32 partial sums of split dK/dV items, [slot][KV head][dK, dV][128 keys][D]
   const int32_t* qbounds;  // backward, or null: [32-row tiles of all blocks + 1][8] bounds of the rows' ranges (RangeBounds order)
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh, dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
@@ -20,6 +22,19 @@ struct KTensors {
   float scale;
   int32_t use_slots;
 };
+
+#ifdef __HIPCC__
+// The range-array entry of packed token i (s0 = first token of its sequence): read from the array, or, for a
+// sliding window with sink, the window [lo, i + 1) with lo = max(i - window + 1, s0) and the sink tokens before it,
+// [s0, min(s0 + sink, lo)) (two ranges that do not overlap).
+__device__ __forceinline__ int4 range_row(const KTensors& t, int i, int s0) {
+  if (t.window > 0) {
+    const int lo = max(i - t.window + 1, s0);
+    return make_int4(s0, min(s0 + t.sink, lo), lo, i + 1);
+  }
+  return ((const int4*)t.ranges)[i];
+}
+#endif
 
 // Optional per-kernel event timing (see dcp_profile_enable).
 struct ProfScope {
@@ -48,8 +63,8 @@ dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s);
 // per 32-row tile of every block: bounds of its rows' range arrays -> qbounds [n_t32 + 1][8]
-dcp_status_t mfma_range_bounds(const int32_t* blk_start, const int32_t* blk_len, const int32_t* blk_t32, int32_t n_blocks,
-                               int32_t block_size, const int32_t* ranges, int32_t* qbounds, hipStream_t s);
+dcp_status_t mfma_range_bounds(const DevGroup& g, const KTensors& t, const int32_t* blk_t32, int32_t n_blocks, int32_t* qbounds,
+                               hipStream_t s);
 
 // streaming (HBM-bound) kernels
 dcp_status_t stream_merge(const int32_t* merge_ptr, const int32_t* merge_idx, const int32_t* blk_mem0,

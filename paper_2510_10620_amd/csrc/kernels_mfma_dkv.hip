@@ -18,21 +18,20 @@ static constexpr int kStageBytes = kStageBounds + 1024;
 // Bounds of the range arrays of every 32-row tile of every block (rows of a tile = lanes 0..31), so that the
 // dK/dV kernel, which streams query tiles past fixed keys, can tell without reading the rows whether a tile
 // sees any of its keys (skip) or all of them (no per-element test).  Entry layout = RangeBounds member order.
-__global__ __launch_bounds__(256) void range_bounds_kernel(const int32_t* __restrict__ blk_start, const int32_t* __restrict__ blk_len,
-                                                           const int32_t* __restrict__ blk_t32, const int4* __restrict__ ranges,
+__global__ __launch_bounds__(256) void range_bounds_kernel(DevGroup g, KTensors t, const int32_t* __restrict__ blk_t32,
                                                            int32_t* __restrict__ qbounds) {
   const int b = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int t = blockIdx.x * 4 + wave;
-  const int len = blk_len[b];
-  if (32 * t >= len) return;
-  const int row = 32 * t + (lane & 31);
+  const int tile = blockIdx.x * 4 + wave;
+  const int len = g.blk_len[b];
+  if (32 * tile >= len) return;
+  const int row = 32 * tile + (lane & 31);
   RangeBounds rb;
   rb.init();
-  if (row < len) rb.add(ranges[blk_start[b] + row]);
+  if (row < len) rb.add(range_row(t, g.blk_start[b] + row, g.blk_s0[b]));
   rb.wave_reduce();
   if (lane == 0) {
-    int32_t* o = qbounds + (int64_t)(blk_t32[b] + t) * 8;
+    int32_t* o = qbounds + (int64_t)(blk_t32[b] + tile) * 8;
     o[0] = rb.lo_min[0]; o[1] = rb.lo_max[0]; o[2] = rb.hi_min[0]; o[3] = rb.hi_max[0];
     o[4] = rb.lo_min[1]; o[5] = rb.lo_max[1]; o[6] = rb.hi_min[1]; o[7] = rb.hi_max[1];
   }
@@ -227,6 +226,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
   const int li = lane & 31, lh = lane >> 5;
   const int blk_start = uni(g.blk_start[kb]), blk_len = uni(g.blk_len[kb]);
   const int koff = uni(g.unit_moff[w.unit]);   // rows of the KV-type buffers: packed index + koff
+  const int seq0 = RANGES ? uni(g.blk_s0[kb]) : 0;   // first token of the sequence (keys and queries share it)
   const int row0 = w.tile * TK;
   const int n_rows = min(TK, blk_len - row0);
   const int k_lo = blk_start + row0, k_end = k_lo + n_rows;
@@ -262,7 +262,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
     const int qmem = qrow + it.moff;
     if (wave == 0) dma4((unsigned)qmem * 4u, uni_ptr(t.lse2 + (int64_t)head * t.q_rows), lds_addr(stage + kStageLse));
     if (wave == 1) dma4((unsigned)qmem * 4u, uni_ptr(t.delta + (int64_t)head * t.q_rows), lds_addr(stage + kStageDelta));
-    if (RANGES && wave == 2 && it.kind == 2) dma16((unsigned)qrow * 16u, uni_ptr(t.ranges), lds_addr(stage + kStageRanges));
+    if (RANGES && wave == 2 && it.kind == 2) {
+      // the rows' ranges: copied from the array, or (WINDOW rows) worked out and stored; the barrier that ends the
+      // step orders the store before the reads
+      if (t.window > 0) *((int4*)(stage + kStageRanges) + lane) = range_row(t, qrow, seq0);
+      else dma16((unsigned)qrow * 16u, uni_ptr(t.ranges), lds_addr(stage + kStageRanges));
+    }
     // the bounds of the tile's two halves (4 x 16 B; the other lanes repeat them into the reserved space)
     if (RANGES && wave == 3 && it.kind == 2 && t.qbounds)
       dma16((unsigned)(lane & 3) * 16u, uni_ptr(t.qbounds + (int64_t)(it.t32 + 2 * it.jt) * 8), lds_addr(stage + kStageBounds));
@@ -368,11 +373,10 @@ __global__ __launch_bounds__(256) void dkv_reduce_kernel(DevGroup g, KTensors t)
   }
 }
 
-dcp_status_t mfma_range_bounds(const int32_t* blk_start, const int32_t* blk_len, const int32_t* blk_t32, int32_t n_blocks,
-                               int32_t block_size, const int32_t* ranges, int32_t* qbounds, hipStream_t s) {
+dcp_status_t mfma_range_bounds(const DevGroup& g, const KTensors& t, const int32_t* blk_t32, int32_t n_blocks, int32_t* qbounds,
+                               hipStream_t s) {
   if (n_blocks == 0) return DCP_OK;
-  hipLaunchKernelGGL(range_bounds_kernel, dim3((block_size + 127) / 128, n_blocks), dim3(256), 0, s, blk_start, blk_len, blk_t32,
-                     (const int4*)ranges, qbounds);
+  hipLaunchKernelGGL(range_bounds_kernel, dim3((t.block_size + 127) / 128, n_blocks), dim3(256), 0, s, g, t, blk_t32, qbounds);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;
 }
@@ -382,7 +386,7 @@ int mfma_dkv_tile() { return 128; }
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
   const int per_xcd = (g.n_items * t.hkv + 7) / 8;
-  if (t.ranges) hipLaunchKernelGGL(mfma_dkv_kernel<true>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  if (t.masked) hipLaunchKernelGGL(mfma_dkv_kernel<true>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   else hipLaunchKernelGGL(mfma_dkv_kernel<false>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   if (g.n_reduce > 0) {

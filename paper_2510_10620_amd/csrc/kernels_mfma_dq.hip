@@ -53,7 +53,7 @@ __device__ __forceinline__ void dq_subtile(DqState& st, const char* k_lds, const
 
 template <bool RANGES>
 __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t) {
-  if (!RANGES) t.ranges = nullptr;
+  if (!RANGES) t.masked = 0;
   constexpr int TM = 128;
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];
   __shared__ __attribute__((aligned(1024))) char stage1[2 * kTileBytes];
@@ -87,12 +87,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   st.qr = make_int4(0, 0, 0, 0);
   RangeBounds wrb;
   wrb.init();
-  if (t.ranges) {
-    st.qr = ((const int4*)t.ranges)[st.qi];
+  if (t.masked) {
+    st.qr = range_row(t, st.qi, uni(g.blk_s0[qb]));
     if (qv) wrb.add(st.qr);
   }
   RangeBounds rb = wrb;
-  if (t.ranges) {
+  if (t.masked) {
     wrb.wave_reduce();
     if (lane == 0) {
       wg_bounds[wave][0] = wrb.lo_min[0]; wg_bounds[wave][1] = wrb.lo_max[0]; wg_bounds[wave][2] = wrb.hi_min[0]; wg_bounds[wave][3] = wrb.hi_max[0];
@@ -179,7 +179,7 @@ int mfma_dq_tile() { return 128; }
 dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
   const int per_xcd = (g.n_items * t.hq + 7) / 8;
-  if (t.ranges) hipLaunchKernelGGL(mfma_dq_kernel<true>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  if (t.masked) hipLaunchKernelGGL(mfma_dq_kernel<true>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   else hipLaunchKernelGGL(mfma_dq_kernel<false>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;

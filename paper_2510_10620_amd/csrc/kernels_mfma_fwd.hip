@@ -190,10 +190,10 @@ __device__ __forceinline__ void fwd_tile64(FwdState<NQ>& st, const char* k_lds, 
       }
 }
 
-// RANGES = false: the table has no RANGES row; t.ranges is null and every use of it folds away.
+// RANGES = false: the table has no row with per-token ranges (RANGES or WINDOW) and every use of them folds away.
 template <int NQ, bool RANGES>
 __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_kernel(DevGroup g, KTensors t) {
-  if (!RANGES) t.ranges = nullptr;
+  if (!RANGES) t.masked = 0;
   constexpr int WR = FwdCfg<NQ>::kWaveRows, TM = FwdCfg<NQ>::kTileM;
   // two stages, each [K tile | V tile]
   __shared__ __attribute__((aligned(1024))) char stage0[2 * kTileBytes];
@@ -231,13 +231,13 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
     qv[nq] = r < n_rows;
     st.qi[nq] = q_lo + min(r, n_rows - 1);
     st.qr[nq] = make_int4(0, 0, 0, 0);
-    if (t.ranges) {
-      st.qr[nq] = ((const int4*)t.ranges)[st.qi[nq]];
+    if (t.masked) {
+      st.qr[nq] = range_row(t, st.qi[nq], uni(g.blk_s0[qb]));
       if (qv[nq]) wrb.add(st.qr[nq]);
     }
   }
   RangeBounds rb = wrb;  // workgroup bounds
-  if (t.ranges) {
+  if (t.masked) {
     wrb.wave_reduce();
     if (lane == 0) {
       wg_bounds[wave][0] = wrb.lo_min[0]; wg_bounds[wave][1] = wrb.lo_max[0]; wg_bounds[wave][2] = wrb.hi_min[0]; wg_bounds[wave][3] = wrb.hi_max[0];
@@ -349,7 +349,7 @@ dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
   const int total = g.n_items * t.hq;
   const int per_xcd = (total + 7) / 8;
-  if (t.ranges) hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, true>), dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
+  if (t.masked) hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, true>), dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
   else hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, false>), dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(kTile) void scalar_fwd_kernel(DevGroup g, KTensors 
   for (int d = 0; d < D; d++) { q[d] = Elem<T>::load(qp + d) * t.scale; acc[d] = 0.f; }
   float m = -INFINITY, l = 0.f;
   int4 r = make_int4(0, 0, 0, 0);
-  if (t.ranges) r = ((const int4*)t.ranges)[i];
+  if (t.masked) r = range_row(t, i, g.blk_s0[qb]);
   for (int e = g.ptr[w.unit]; e < g.ptr[w.unit + 1]; e++) {
     const int c0 = g.ent_start[e], c1 = c0 + g.ent_len[e], kind = g.ent_kind[e], km = g.ent_moff[e];
     for (int j = c0; j < c1; j++) {
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kTile) void scalar_dq_kernel(DevGroup g, KTensors t
   const float delta = t.delta[(int64_t)h * t.q_rows + im];
   const bool row_on = valid && lse > -INFINITY;
   int4 r = make_int4(0, 0, 0, 0);
-  if (t.ranges) r = ((const int4*)t.ranges)[i];
+  if (t.masked) r = range_row(t, i, g.blk_s0[qb]);
   for (int e = g.ptr[w.unit]; e < g.ptr[w.unit + 1]; e++) {
     const int c0 = g.ent_start[e], c1 = c0 + g.ent_len[e], kind = g.ent_kind[e], km = g.ent_moff[e];
     for (int j = c0; j < c1; j++) {
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kTile) void scalar_dkv_kernel(DevGroup g, KTensors 
       const int q0 = g.ent_start[e], q1 = q0 + g.ent_len[e], kind = g.ent_kind[e], qm = g.ent_moff[e];
       for (int i = q0; i < q1; i++) {
         int4 r = make_int4(0, 0, 0, 0);
-        if (kind == 2) r = ((const int4*)t.ranges)[i];
+        if (kind == 2) r = range_row(t, i, g.blk_s0[kb]);   // same sequence as the key block
         const float lse = t.lse[(int64_t)h * t.q_rows + i + qm];
         const bool vis = valid && lse > -INFINITY && key_visible(kind, i, j, r);
         if (!__any(vis)) continue;

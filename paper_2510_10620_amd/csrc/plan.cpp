@@ -57,13 +57,29 @@ using namespace dcp;
 
 extern "C" const char* dcp_last_error(void) { return g_err.c_str(); }
 
-extern "C" dcp_status_t dcp_build_block_table(const int32_t* cu, int32_t n_seq, int32_t B, const int32_t* ranges,
-                                              int32_t* table_out, int64_t capacity, int64_t* n_out) {
-  if (!n_out) return fail(DCP_ERR_INVALID_ARG, "n_entries_out is NULL");
-  Partition p;
-  dcp_status_t st = make_partition(cu, n_seq, B, &p);
-  if (st != DCP_OK) return st;
-  if (!ranges && n_seq > 0) return fail(DCP_ERR_INVALID_ARG, "attn_ranges is NULL");
+// Per-token ranges of a sliding window with sink: the window [lo, i + 1), lo = max(i - window + 1, s0), and the
+// sink tokens before it, [s0, min(s0 + sink, lo)).
+static std::vector<int32_t> window_ranges(const int32_t* cu, int32_t n_seq, int64_t window, int64_t sink) {
+  std::vector<int32_t> r((size_t)(n_seq > 0 ? cu[n_seq] : 0) * 4);
+  for (int32_t s = 0; s < n_seq; s++)
+    for (int64_t i = cu[s]; i < cu[s + 1]; i++) {
+      const int64_t lo = std::max<int64_t>(i - window + 1, cu[s]);
+      r[4 * i] = cu[s];
+      r[4 * i + 1] = (int32_t)std::min<int64_t>(cu[s] + sink, lo);
+      r[4 * i + 2] = (int32_t)lo;
+      r[4 * i + 3] = (int32_t)(i + 1);
+    }
+  return r;
+}
+
+static dcp_status_t check_window(int32_t window, int32_t sink) {
+  if (window < 1 || window > (1 << 30)) return fail(DCP_ERR_INVALID_ARG, "window must lie in [1, 2^30]");
+  if (sink < 0 || sink > (1 << 30)) return fail(DCP_ERR_INVALID_ARG, "sink must lie in [0, 2^30]");
+  return DCP_OK;
+}
+
+static dcp_status_t build_table(const Partition& p, int32_t n_seq, const int32_t* ranges, int32_t other_kind,
+                                int32_t* table_out, int64_t capacity, int64_t* n_out) {
   int64_t n = 0;
   for (int32_t s = 0; s < n_seq; s++) {
     for (int32_t qb = p.first[s]; qb < p.first[s + 1]; qb++) {
@@ -82,7 +98,7 @@ extern "C" dcp_status_t dcp_build_block_table(const int32_t* cu, int32_t n_seq, 
           causal &= (nvis == want) && (row_visible(r, c0, c0 + want) == want);
         }
         if (!any) continue;
-        int32_t kind = all ? DCP_MASK_NONE : (causal ? DCP_MASK_CAUSAL : DCP_MASK_RANGES);
+        int32_t kind = all ? DCP_MASK_NONE : (causal ? DCP_MASK_CAUSAL : other_kind);
         if (table_out && n < capacity) {
           table_out[3 * n + 0] = qb;
           table_out[3 * n + 1] = kb;
@@ -95,6 +111,43 @@ extern "C" dcp_status_t dcp_build_block_table(const int32_t* cu, int32_t n_seq, 
   *n_out = n;
   if (table_out && n > capacity) return fail(DCP_ERR_INVALID_ARG, "block table capacity too small");
   return DCP_OK;
+}
+
+extern "C" dcp_status_t dcp_build_block_table(const int32_t* cu, int32_t n_seq, int32_t B, const int32_t* ranges,
+                                              int32_t* table_out, int64_t capacity, int64_t* n_out) {
+  if (!n_out) return fail(DCP_ERR_INVALID_ARG, "n_entries_out is NULL");
+  Partition p;
+  dcp_status_t st = make_partition(cu, n_seq, B, &p);
+  if (st != DCP_OK) return st;
+  if (!ranges && n_seq > 0) return fail(DCP_ERR_INVALID_ARG, "attn_ranges is NULL");
+  return build_table(p, n_seq, ranges, DCP_MASK_RANGES, table_out, capacity, n_out);
+}
+
+extern "C" dcp_status_t dcp_build_block_table_window(const int32_t* cu, int32_t n_seq, int32_t B, int32_t window, int32_t sink,
+                                                     int32_t* table_out, int64_t capacity, int64_t* n_out) {
+  if (!n_out) return fail(DCP_ERR_INVALID_ARG, "n_entries_out is NULL");
+  Partition p;
+  dcp_status_t st = make_partition(cu, n_seq, B, &p);
+  if (st != DCP_OK) return st;
+  if ((st = check_window(window, sink)) != DCP_OK) return st;
+  const std::vector<int32_t> r = window_ranges(cu, n_seq, window, sink);
+  return build_table(p, n_seq, r.data(), DCP_MASK_WINDOW, table_out, capacity, n_out);
+}
+
+extern "C" dcp_status_t dcp_count_pairs_window(const int32_t* cu, int32_t n_seq, int32_t B, const int32_t* table,
+                                               int64_t n_entries, int32_t window, int32_t sink, int64_t* pairs_out) {
+  Partition p;
+  dcp_status_t st = make_partition(cu, n_seq, B, &p);
+  if (st != DCP_OK) return st;
+  if ((st = check_window(window, sink)) != DCP_OK) return st;
+  if (n_entries < 0 || (n_entries > 0 && (!table || !pairs_out))) return fail(DCP_ERR_INVALID_ARG, "bad table / output pointer");
+  std::vector<int32_t> t2(table, table + 3 * n_entries);
+  for (int64_t e = 0; e < n_entries; e++) {
+    if (t2[3 * e + 2] == DCP_MASK_RANGES) return fail(DCP_ERR_BAD_TABLE, "RANGES row in a WINDOW table");
+    if (t2[3 * e + 2] == DCP_MASK_WINDOW) t2[3 * e + 2] = DCP_MASK_RANGES;
+  }
+  const std::vector<int32_t> r = window_ranges(cu, n_seq, window, sink);
+  return dcp_count_pairs(cu, n_seq, B, t2.data(), n_entries, r.data(), pairs_out);
 }
 
 extern "C" dcp_status_t dcp_count_pairs(const int32_t* cu, int32_t n_seq, int32_t B, const int32_t* table,
@@ -143,7 +196,7 @@ extern "C" dcp_status_t dcp_comm_volume(const int32_t* cu, int32_t n_seq, int32_
   int64_t pw = 0;
   for (int64_t e = 0; e < n_entries; e++) {
     const int32_t qb = table[3 * e], kb = table[3 * e + 1], kind = table[3 * e + 2], d = comp_dev[e];
-    if (kind < 0 || kind > 3) return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": bad mask_kind");
+    if (kind < 0 || kind > 4) return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": bad mask_kind");
     if (qb < 0 || qb >= nb || kb < 0 || kb >= nb) return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": block id out of range");
     if (kind == DCP_MASK_SKIP) continue;
     if (d < 0 || d >= n_devices) return fail(DCP_ERR_BAD_TABLE, "comp_dev[" + std::to_string(e) + "] out of range");
@@ -240,7 +293,7 @@ extern "C" dcp_status_t dcp_plan_create(dcp_plan_t** out, const int32_t* cu, int
   std::set<std::pair<int32_t, int32_t>> seen;
   for (int64_t e = 0; e < n_entries; e++) {
     int32_t qb = table[3 * e], kb = table[3 * e + 1], kind = table[3 * e + 2];
-    if (kind < 0 || kind > 3) return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": bad mask_kind");
+    if (kind < 0 || kind > 4) return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": bad mask_kind");
     if (qb < 0 || qb >= pl->n_blocks || kb < 0 || kb >= pl->n_blocks)
       return fail(DCP_ERR_BAD_TABLE, "row " + std::to_string(e) + ": block id out of range");
     if (p.seq[qb] != p.seq[kb])
@@ -257,6 +310,8 @@ extern "C" dcp_status_t dcp_plan_create(dcp_plan_t** out, const int32_t* cu, int
       sq = qb;
     }
     if (kind == DCP_MASK_RANGES) pl->has_ranges = true;
+    if (kind == DCP_MASK_WINDOW) pl->has_window = true;
+    if (pl->has_ranges && pl->has_window) return fail(DCP_ERR_BAD_TABLE, "a table holds RANGES rows or WINDOW rows, not both");
     kept.push_back(e);
   }
   pl->n_kept = (int64_t)kept.size();
@@ -342,6 +397,16 @@ extern "C" dcp_status_t dcp_plan_set_block_buffers(dcp_plan_t* plan, const int32
   return DCP_OK;
 }
 
+extern "C" dcp_status_t dcp_plan_set_window(dcp_plan_t* plan, int32_t window, int32_t sink) {
+  if (!plan) return fail(DCP_ERR_INVALID_ARG, "plan is NULL");
+  dcp_status_t st = check_window(window, sink);
+  if (st != DCP_OK) return st;
+  std::lock_guard<std::mutex> lock(plan->mu);
+  plan->window = window;
+  plan->sink = sink;
+  return DCP_OK;
+}
+
 extern "C" dcp_status_t dcp_plan_destroy(dcp_plan_t* plan) {
   if (!plan) return DCP_OK;
   if (plan->dev_arena || !plan->items.empty()) {
@@ -403,7 +468,9 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     while (host.size() % 4) host.push_back(0);
     return off;
   };
-  size_t o_bs = put(blk_start), o_bl = put(blk_len);
+  std::vector<int32_t> blk_s0(n_blocks);
+  for (int32_t b = 0; b < n_blocks; b++) blk_s0[b] = cu[blk_seq[b]];
+  size_t o_bs = put(blk_start), o_bl = put(blk_len), o_s0 = put(blk_s0);
   struct Off { size_t ub, uo, ptr, es, el, ek, um, em, et, er; } go[3];
   HostGroup* gs[3] = {&fwd, &bwdq, &bwdkv};
   for (int i = 0; i < 3; i++) {
@@ -415,12 +482,16 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
       if (gs[i]->unit_blk[u] >= 0) um[u] = own[gs[i]->unit_blk[u]];
     std::vector<int32_t> et(gs[i]->ent_blk.size(), 0);
     for (size_t e = 0; e < em.size(); e++) { em[e] = other[gs[i]->ent_blk[e]]; et[e] = blk_t32[gs[i]->ent_blk[e]]; }
-    go[i] = {put(gs[i]->unit_blk), put(gs[i]->unit_out), put(gs[i]->ptr), put(gs[i]->ent_start), put(gs[i]->ent_len), put(gs[i]->ent_kind),
+    // on the device a WINDOW row is a row with per-token ranges like a RANGES row; only where the ranges come from differs
+    std::vector<int32_t> dk(gs[i]->ent_kind);
+    for (int32_t& k : dk)
+      if (k == DCP_MASK_WINDOW) k = DCP_MASK_RANGES;
+    go[i] = {put(gs[i]->unit_blk), put(gs[i]->unit_out), put(gs[i]->ptr), put(gs[i]->ent_start), put(gs[i]->ent_len), put(dk),
              put(um), put(em), put(et), 0};
     {
       std::vector<int32_t> rec(gs[i]->ent_blk.size() * 8, 0);
       for (size_t e = 0; e < em.size(); e++) {
-        rec[8 * e] = gs[i]->ent_start[e]; rec[8 * e + 1] = gs[i]->ent_len[e]; rec[8 * e + 2] = gs[i]->ent_kind[e];
+        rec[8 * e] = gs[i]->ent_start[e]; rec[8 * e + 1] = gs[i]->ent_len[e]; rec[8 * e + 2] = dk[e];
         rec[8 * e + 3] = em[e]; rec[8 * e + 4] = et[e];
       }
       while (host.size() % 8) host.push_back(0);   // records are read as 16-byte vectors
@@ -456,6 +527,7 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     ds[i]->ent_rec = dev_arena + go[i].er;
     ds[i]->blk_start = dev_arena + o_bs;
     ds[i]->blk_len = dev_arena + o_bl;
+    ds[i]->blk_s0 = dev_arena + o_s0;
     ds[i]->items = nullptr;
     ds[i]->reduce = nullptr;
     ds[i]->n_items = 0;

@@ -18,7 +18,7 @@ from typing import Dict, List, Optional, Tuple
 import numpy as np
 
 # mask_kind codes of the block table (a row is q_blk, kv_blk, mask_kind)
-MASK_NONE, MASK_CAUSAL, MASK_RANGES, MASK_SKIP = 0, 1, 2, 3
+MASK_NONE, MASK_CAUSAL, MASK_RANGES, MASK_SKIP, MASK_WINDOW = 0, 1, 2, 3, 4
 
 
 @dataclass(frozen=True)

@@ -30,17 +30,20 @@ def from_torch(x):
 class GpuRun:
     """Holds device tensors of one workload and runs forward / merge / backward via the C ABI."""
 
-    def __init__(self, w, tensors, table, out_slot=None, n_slots=0, impl=0):
+    def __init__(self, w, tensors, table, out_slot=None, n_slots=0, impl=0, window=None):
+        """window = (window, sink): the table has WINDOW rows; no range array is passed to the library."""
         import torch
         import paper_2510_10620_amd as P
         self.P, self.torch, self.w, self.impl = P, torch, w, impl
         self.table = np.asarray(table, dtype=np.int32).reshape(-1, 3)
         self.plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, self.table, out_slot, n_slots)
+        if window is not None:
+            P.dcp_plan_set_window(self.plan, *window)
         self.use_slots = out_slot is not None
         self.n_slots = n_slots
         self.q, self.k, self.v = (to_torch(w, tensors[n]) for n in ("q", "k", "v"))
         self.dout = to_torch(w, tensors["dout"]) if "dout" in tensors else None
-        self.ranges = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+        self.ranges = None if window is not None else torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
         T = w.total_tokens
         self.out = torch.full((T, w.hq, w.d), float("nan"), dtype=self.q.dtype, device="cuda")
         self.lse = torch.full((w.hq, T), float("nan"), dtype=torch.float32, device="cuda")
@@ -100,7 +103,7 @@ class GpuRun:
         return from_torch(self.dq), from_torch(self.dk), from_torch(self.dv)
 
 
-def oracle_full(w, tensors, table, select=None, lse=None, delta=None, bwd=True, seqs=None, heads=None):
+def oracle_full(w, tensors, table, select=None, lse=None, delta=None, bwd=True, seqs=None, heads=None, window=None):
     """Oracle forward (+ backward) on the full tensors, or on q heads `heads` (a list that must
     cover whole KV groups' worth of the heads it names: heads are given as (q_heads, kv_head))."""
     q, k, v = (W.to_f64(w, tensors[n]) for n in ("q", "k", "v"))
@@ -111,7 +114,7 @@ def oracle_full(w, tensors, table, select=None, lse=None, delta=None, bwd=True, 
         do = do[:, qh] if do is not None else None
         lse = lse[qh] if lse is not None else None
         delta = delta[qh] if delta is not None else None
-    vis = OB.Visibility(w.cu_seqlens, w.block_size, table, w.ranges, select=select)
+    vis = OB.Visibility(w.cu_seqlens, w.block_size, table, None if window is not None else w.ranges, select=select, window=window)
     O, LSE = OA.attention_fwd(q, k, v, w.cu_seqlens, vis, w.softmax_scale, seqs=seqs)
     res = dict(out=O, lse=LSE)
     if bwd:
@@ -136,14 +139,18 @@ def max_abs(a, b):
     return float(np.nan_to_num(d, nan=np.inf, posinf=np.inf).max())
 
 
-def max_scaled(a, b, knee):
+def max_scaled(a, b, knee, by_row=False):
     """max |a - b| / max(1, |b| / knee): the absolute error where |b| <= knee, and the error
-    relative to |b| / knee above it."""
+    relative to |b| / knee above it.  by_row: |b| is replaced by the largest |b| of the element's
+    row (last axis)."""
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
     cmp = _cmp_mask(a, b)
     if not cmp.any():
         return 0.0
-    d = np.abs(a[cmp] - b[cmp]) / np.maximum(1.0, np.abs(b[cmp]) / knee)
+    mag = np.abs(b)
+    if by_row:
+        mag = np.broadcast_to(np.where(np.isfinite(mag), mag, 0.0).max(axis=-1, keepdims=True), b.shape)
+    d = np.abs(a[cmp] - b[cmp]) / np.maximum(1.0, mag[cmp] / knee)
     return float(np.nan_to_num(d, nan=np.inf, posinf=np.inf).max())
 
 
@@ -152,17 +159,21 @@ def max_scaled(a, b, knee):
 # (half an ulp is 2^-8 |x|: 0.0156 on [4, 8), 0.031 on [8, 16)), and the bf16 rounding of the
 # P / dS MFMA operands adds its own accumulated share, so the bound grows in proportion to the
 # magnitude: 2e-2 * |ref| / 2 = 1e-2 |ref|, about 2.5 bf16 half-ulps.
+# by_row (only where a test says why): a gradient row that sums very many large terms which cancel.
+# All D elements of the row share the coefficients (P or dS) whose rounding to bf16 makes the error, so
+# the error of every element is about 2^-9 of the row's root-mean-square, whatever the element's own
+# value; the row's largest |ref| (2.5-3 rms) then takes the place of |ref| in the bound above.
 TOL = {"bf16": dict(o=2e-2, lse=1e-5, knee=2.0), "f32": dict(o=1e-4, lse=1e-5, knee=None)}
 
 
-def check(w, got, ref, names, label="", verbose=False):
+def check(w, got, ref, names, label="", verbose=False, by_row=False):
     tol = TOL[w.dtype]
     errs = {}
     for n in names:
         if n == "lse" or tol["knee"] is None:
             err, lim = max_abs(got[n], ref[n]), (tol["lse"] if n == "lse" else tol["o"])
         else:
-            err, lim = max_scaled(got[n], ref[n], tol["knee"]), tol["o"]
+            err, lim = max_scaled(got[n], ref[n], tol["knee"], by_row), tol["o"]
         errs[n] = err
         assert err <= lim, f"{label} {n}: max err {err:.3e} > {lim:.1e}"
     if verbose:

@@ -176,3 +176,27 @@ def test_full_size_config(cfg):
     dk_max = g.dk.float().abs().max().item()
     print(f"cfg{cfg} Q=0 closed form: out {o_err:.2e} lse {lse_err:.2e} dv(scaled) {dv_err:.2e} |dk| {dk_max:.2e}", flush=True)
     assert o_err <= 2e-2 and lse_err <= 1e-5 and dv_err <= 2e-2 and dk_max <= 2e-2
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_full_size_window_kind_is_the_ranges_route_bit_for_bit(cfg):
+    """Configs 3 (window 4096) and 4 (window 8192, 64 sink tokens) through WINDOW rows, which take two numbers instead
+    of the [T, 4] range array: the kernels work out the same per-token ranges, so every output must equal, bit for
+    bit, what the RANGES route gives on the same batch (that route is checked against the oracle above)."""
+    import torch
+    import paper_2510_10620_amd as P
+    w = W.make_workload(cfg)
+    tensors = W.make_tensors(w)
+    t_rng = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+    t_win = P.dcp_build_block_table_window(w.cu_seqlens, w.block_size, w.mask.window, w.mask.sink)
+    assert np.array_equal(t_win[:, :2], t_rng[:, :2])
+    assert np.array_equal(np.where(t_win[:, 2] == W.MASK_WINDOW, W.MASK_RANGES, t_win[:, 2]), t_rng[:, 2])
+    assert int(P.dcp_count_pairs_window(w.cu_seqlens, w.block_size, t_win, w.mask.window, w.mask.sink).sum()) == \
+        int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, t_rng, w.ranges).sum())
+    a = H.GpuRun(w, tensors, t_rng)
+    b = H.GpuRun(w, tensors, t_win, window=(w.mask.window, w.mask.sink))
+    for g in (a, b):
+        g.forward_only()
+        g.backward_only(g.out, g.lse)
+    for name in ("out", "lse", "dq", "dk", "dv"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name

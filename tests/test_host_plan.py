@@ -156,6 +156,35 @@ def test_dkv_work_list_is_an_exact_partition(spec, lens, B, hkv):
     assert full - base == len(slots) * hkv * 2 * 128 * 128 * 4
 
 
+@pytest.mark.parametrize("window,sink", [(50, 0), (40, 7), (16, 16), (1, 0), (300, 3), (5, 400)])
+def test_window_table_and_pair_counts_bit_exact_vs_oracle(window, sink):
+    rng = np.random.default_rng(29)
+    lens = [int(x) for x in rng.integers(20, 200, size=4)] + [1, 16]
+    B = 16
+    cu = W.cu_from_lengths(lens)
+    spec = W.MaskSpec("lambda", window=window, sink=sink) if sink else W.MaskSpec("window", window=window)
+    want = OB.table_from_mask(lambda s, L, r0, r1: OM.dense_rows(spec, L, r0, r1), cu, B, other_kind=OB.MASK_WINDOW)
+    got = P.dcp_build_block_table_window(cu, B, window, sink)
+    assert np.array_equal(got, want)
+    counts = OB.Visibility(cu, B, want, window=(window, sink)).pair_counts()
+    assert np.array_equal(P.dcp_count_pairs_window(cu, B, got, window, sink), counts)
+
+
+def test_window_kind_error_paths():
+    cu = W.cu_from_lengths([64, 64])
+    t_win = np.array([[0, 0, P.DCP_MASK_WINDOW], [1, 1, P.DCP_MASK_CAUSAL]], dtype=np.int32)
+    plan = P.dcp_plan_create(cu, 64, t_win)
+    assert _status(P.dcp_plan_set_window, plan, 0, 0) == P.DCP_ERR_INVALID_ARG
+    assert _status(P.dcp_plan_set_window, plan, 5, -1) == P.DCP_ERR_INVALID_ARG
+    P.dcp_plan_set_window(plan, 5, 2)
+    mixed = np.array([[0, 0, P.DCP_MASK_WINDOW], [1, 1, P.DCP_MASK_RANGES]], dtype=np.int32)
+    assert _status(P.dcp_plan_create, cu, 64, mixed) == P.DCP_ERR_BAD_TABLE
+    assert _status(P.dcp_plan_create, cu, 64, np.array([[0, 0, 5]], dtype=np.int32)) == P.DCP_ERR_BAD_TABLE
+    assert _status(P.dcp_build_block_table_window, cu, 64, 0, 0) == P.DCP_ERR_INVALID_ARG
+    assert _status(P.dcp_count_pairs_window, cu, 64, mixed, 5, 0) == P.DCP_ERR_BAD_TABLE
+    assert _status(P.dcp_count_pairs, cu, 64, t_win) == P.DCP_ERR_BAD_TABLE      # WINDOW rows need the window counter
+
+
 def _status(fn, *a, **k):
     with pytest.raises(P.DcpError) as ei:
         fn(*a, **k)
@@ -174,7 +203,7 @@ def test_error_paths():
     assert _status(P.dcp_plan_create, cu, 8, np.array([[0, 3, 0]], np.int32)) == P.DCP_ERR_BAD_TABLE     # id out of range
     assert _status(P.dcp_plan_create, cu, 8, np.array([[-1, 0, 0]], np.int32)) == P.DCP_ERR_BAD_TABLE
     assert _status(P.dcp_plan_create, cu, 8, np.array([[0, 2, 0]], np.int32)) == P.DCP_ERR_BAD_TABLE     # two sequences
-    assert _status(P.dcp_plan_create, cu, 8, np.array([[0, 0, 4]], np.int32)) == P.DCP_ERR_BAD_TABLE     # bad kind
+    assert _status(P.dcp_plan_create, cu, 8, np.array([[0, 0, 5]], np.int32)) == P.DCP_ERR_BAD_TABLE     # bad kind
     assert _status(P.dcp_plan_create, cu, 8, np.array([[1, 0, 0], [1, 0, 1]], np.int32)) == P.DCP_ERR_BAD_TABLE  # duplicate
     P.dcp_plan_create(cu, 8, np.array([[1, 0, 0], [1, 0, 3]], np.int32))                                  # SKIP duplicate is ignored
     two = np.array([[0, 0, 1], [1, 0, 0]], np.int32)
