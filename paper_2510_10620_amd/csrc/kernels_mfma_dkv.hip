@@ -155,10 +155,27 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
   f32x16 s, dp;
 #pragma unroll
   for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+  if constexpr (!RANGES) {
+    // operands one k-step ahead of the MFMAs that use them (8 more registers in flight, -6 %; the kernel for tables
+    // with per-token ranges has no registers left for it: it spills and gets slower); the fences keep the requests in
+    // front of the MFMAs of the step before
+    bf16x8 qa = frag_rm2(q_lds, fa, 32 * qt, 0), da = frag_rm2(do_lds, fa, 32 * qt, 0);
 #pragma unroll
-  for (int ksd = 0; ksd < 8; ksd++) {
-    s = mfma(frag_rm2(q_lds, fa, 32 * qt, ksd), st.kf[ksd], s);
-    dp = mfma(frag_rm2(do_lds, fa, 32 * qt, ksd), st.vf[ksd], dp);
+    for (int ksd = 0; ksd < 8; ksd++) {
+      bf16x8 qn = qa, dn = da;
+      if (ksd < 7) { qn = frag_rm2(q_lds, fa, 32 * qt, ksd + 1); dn = frag_rm2(do_lds, fa, 32 * qt, ksd + 1); }
+      __builtin_amdgcn_sched_barrier(0);
+      s = mfma(qa, st.kf[ksd], s);
+      dp = mfma(da, st.vf[ksd], dp);
+      qa = qn; da = dn;
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+#pragma unroll
+    for (int ksd = 0; ksd < 8; ksd++) {
+      s = mfma(frag_rm2(q_lds, fa, 32 * qt, ksd), st.kf[ksd], s);
+      dp = mfma(frag_rm2(do_lds, fa, 32 * qt, ksd), st.vf[ksd], dp);
+    }
   }
   if (MASK) {
     // Lane l works out, once, which of the wave's 32 keys query row (l & 31) of the sub-tile sees, as a bit mask
@@ -199,13 +216,35 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
       dp[r] = p * (dp[r] - dv4[b]);
     }
   }
+  if constexpr (!RANGES) {
+    // P and dS packed first (s and dp are dead after that), then the transposed operands one step ahead
+    bf16x8 pb[2], dsb[2];
 #pragma unroll
-  for (int c = 0; c < 2; c++) {
-    const bf16x8 pb = pack_frag(s, c), dsb = pack_frag(dp, c);
+    for (int c = 0; c < 2; c++) { pb[c] = pack_frag(s, c); dsb[c] = pack_frag(dp, c); }
+    bf16x8 ta = frag_tr2(do_lds, fa, 32 * qt, 0), tb = frag_tr2(q_lds, fa, 32 * qt, 0);
 #pragma unroll
-    for (int dt = 0; dt < 4; dt++) {
-      st.dv[dt] = mfma(frag_tr2(do_lds, fa, 32 * qt + 16 * c, dt), pb, st.dv[dt]);
-      st.dk[dt] = mfma(frag_tr2(q_lds, fa, 32 * qt + 16 * c, dt), dsb, st.dk[dt]);
+    for (int i = 0; i < 8; i++) {
+      const int c = i >> 2, dt = i & 3;
+      bf16x8 tan = ta, tbn = tb;
+      if (i < 7) {
+        tan = frag_tr2(do_lds, fa, 32 * qt + 16 * ((i + 1) >> 2), (i + 1) & 3);
+        tbn = frag_tr2(q_lds, fa, 32 * qt + 16 * ((i + 1) >> 2), (i + 1) & 3);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      st.dv[dt] = mfma(ta, pb[c], st.dv[dt]);
+      st.dk[dt] = mfma(tb, dsb[c], st.dk[dt]);
+      ta = tan; tb = tbn;
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 2; c++) {
+      const bf16x8 pb = pack_frag(s, c), dsb = pack_frag(dp, c);
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) {
+        st.dv[dt] = mfma(frag_tr2(do_lds, fa, 32 * qt + 16 * c, dt), pb, st.dv[dt]);
+        st.dk[dt] = mfma(frag_tr2(q_lds, fa, 32 * qt + 16 * c, dt), dsb, st.dk[dt]);
+      }
     }
   }
 }
