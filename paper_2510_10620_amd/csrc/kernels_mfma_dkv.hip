@@ -156,9 +156,9 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
 #pragma unroll
   for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
   if constexpr (!RANGES) {
-    // operands one k-step ahead of the MFMAs that use them (8 more registers in flight, -6 %; the kernel for tables
-    // with per-token ranges has no registers left for it: it spills and gets slower); the fences keep the requests in
-    // front of the MFMAs of the step before
+    // operands one k-step ahead of the MFMAs that use them (8 more registers in flight; the kernel for tables with
+    // per-token ranges has no registers left for it here, where s and dp are live: it spills and gets slower); the
+    // fences keep the requests in front of the MFMAs of the step before
     bf16x8 qa = frag_rm2(q_lds, fa, 32 * qt, 0), da = frag_rm2(do_lds, fa, 32 * qt, 0);
 #pragma unroll
     for (int ksd = 0; ksd < 8; ksd++) {
@@ -216,7 +216,7 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
       dp[r] = p * (dp[r] - dv4[b]);
     }
   }
-  if constexpr (!RANGES) {
+  {
     // P and dS packed first (s and dp are dead after that), then the transposed operands one step ahead
     bf16x8 pb[2], dsb[2];
 #pragma unroll
@@ -235,16 +235,6 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
       st.dk[dt] = mfma(tb, dsb[c], st.dk[dt]);
       ta = tan; tb = tbn;
       __builtin_amdgcn_sched_barrier(0);
-    }
-  } else {
-#pragma unroll
-    for (int c = 0; c < 2; c++) {
-      const bf16x8 pb = pack_frag(s, c), dsb = pack_frag(dp, c);
-#pragma unroll
-      for (int dt = 0; dt < 4; dt++) {
-        st.dv[dt] = mfma(frag_tr2(do_lds, fa, 32 * qt + 16 * c, dt), pb, st.dv[dt]);
-        st.dk[dt] = mfma(frag_tr2(q_lds, fa, 32 * qt + 16 * c, dt), dsb, st.dk[dt]);
-      }
     }
   }
 }
