@@ -105,6 +105,14 @@ template <int NQ>
 __device__ __forceinline__ void fwd_softmax_pv(FwdState<NQ>& st, f32x16 (&s)[2][NQ], bool on0, bool on1, const char* v_lds,
                                                float c_log2) {
   bf16x8 p[2][NQ][2];
+  // V^T fragments of the first 16 keys that will be used, requested before the exponentials, which hide their latency
+  bf16x8 va[4];
+  {
+    const char* v_first = v_lds + (on0 ? 0 : 32 * kRowBytes);
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) va[dt] = frag_tr(v_first, st.fa, 0, dt);
+  }
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int nq = 0; nq < NQ; nq++) {
     float mx = fmaxf(fmaxf(s[0][nq][0], s[0][nq][1]), s[1][nq][0]);
@@ -150,11 +158,15 @@ __device__ __forceinline__ void fwd_softmax_pv(FwdState<NQ>& st, f32x16 (&s)[2][
 #pragma unroll
   for (int kt = 0; kt < 2; kt++) {
     if (!(kt ? on1 : on0)) continue;
+    if (kt == 1 && on0) {   // va held sub-tile 0's fragments (only loads inside this branch, no accumulator)
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) va[dt] = frag_tr(v_lds, st.fa, 32, dt);
+    }
 #pragma unroll
     for (int c = 0; c < 2; c++)
 #pragma unroll
       for (int dt = 0; dt < 4; dt++) {
-        const bf16x8 a = frag_tr(v_lds, st.fa, 32 * kt + 16 * c, dt);
+        const bf16x8 a = c == 0 ? va[dt] : frag_tr(v_lds, st.fa, 32 * kt + 16, dt);
 #pragma unroll
         for (int nq = 0; nq < NQ; nq++) st.o[nq][dt] = mfma(a, p[kt][nq][c], st.o[nq][dt]);
       }
