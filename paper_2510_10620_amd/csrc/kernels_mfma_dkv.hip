@@ -47,10 +47,13 @@ struct QIter {
   int moff;  // the Q block's rows sit at (packed index + moff) in the Q-type buffers
   int t32;   // index of the Q block's first 32-row tile in qbounds
   int qs;    // first query of the current tile
-  // [e0, e1): the table rows of the unit this workgroup covers
+  // [e0, e1): the table rows of the unit this workgroup covers.  They, and the query tiles of each, are walked from
+  // the last to the first: the key tiles of one sequence that start together then stream the same Q / dO rows at
+  // the same time (each is a prefix of one common order) and share them in the L2; walked forwards, each tile would
+  // start at its own diagonal, two steps behind its neighbour, which is as far apart as the L2 is large.
   __device__ QIter(const DevGroup& g, int e0, int e1, int G_, const int32_t* qb)
       : rec((const int4*)g.ent_rec), qbounds((const int4*)qb) {
-    e = e0 - 1; e_end = e1; hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; moff = 0; t32 = 0; qs = 0;
+    e = e1; e_end = e0; hh = G_ - 1; G = G_; jt = 0; n_t = 0; jt0 = 0; q0 = q1 = kind = 0; moff = 0; t32 = 0; qs = 0;
   }
   // Which of the (at most 64) 64-query tiles of the current RANGES row may see a key of [k_lo, k_end): lane l merges
   // the bounds of the two 32-row halves of tile l.  Returns the ballot (wave-uniform).
@@ -74,12 +77,12 @@ struct QIter {
   // keys (tiles inside the span that see nothing are left to the per-sub-tile test).
   __device__ bool next(int k_lo, int k_end) {
     for (;;) {
-      jt++;
-      if (jt >= n_t) {
+      jt--;
+      if (jt < jt0) {
         hh++;
         if (hh >= G) {
-          e++;
-          if (e >= e_end) return false;
+          e--;
+          if (e < e_end) return false;
           hh = 0;
           const int4 r = rec[2 * e];
           q0 = uni(r.x); q1 = q0 + uni(r.y); kind = uni(r.z); moff = uni(r.w); t32 = uni(rec[2 * e + 1].x);
@@ -91,7 +94,7 @@ struct QIter {
             else { jt0 = __builtin_ctzll(m); n_t = 64 - __builtin_clzll(m); }
           }
         }
-        jt = jt0 - 1;
+        jt = n_t;   // one past the last tile of the row
         continue;
       }
       qs = q0 + jt * kTN;
