@@ -21,10 +21,11 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I
           "-Wno-unused-result", "-Wno-unknown-warning-option"]
 
 
-# Per-file instruction-scheduling strategy of the AMDGPU backend, chosen by measurement on MI355X: the dK/dV kernel
-# (one wave per SIMD) gains 4 % from max-ilp, the dQ kernel 2 % from iterative-ilp; the forward is best with the default.
+# Per-file instruction-scheduling strategy of the AMDGPU backend, chosen by measurement on MI355X: the dQ kernel gains
+# 2-3 % from iterative-ilp, the dK/dV variant for tables with per-token ranges up to 3 % from max-ilp (without it the
+# variant for NONE / CAUSAL tables is 1.5 % faster); the forward is best with the default.
 PER_FILE_FLAGS = {
-    "kernels_mfma_dkv.hip": ["-mllvm", "-amdgpu-sched-strategy=max-ilp"],
+    "kernels_mfma_dkv_ranges.hip": ["-mllvm", "-amdgpu-sched-strategy=max-ilp"],
     "kernels_mfma_dq.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"],
 }
 

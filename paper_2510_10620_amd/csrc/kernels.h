@@ -62,6 +62,7 @@ size_t mfma_dkv_part_bytes(int32_t n_pslots, int32_t hkv);   // size of KTensors
 dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s);
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s);
+void mfma_dkv_launch_ranges(const DevGroup& g, const KTensors& t, int grid, hipStream_t s);   // kernels_mfma_dkv_ranges.hip
 // per 32-row tile of every block: bounds of its rows' range arrays -> qbounds [n_t32 + 1][8]
 dcp_status_t mfma_range_bounds(const DevGroup& g, const KTensors& t, const int32_t* blk_t32, int32_t n_blocks, int32_t* qbounds,
                                hipStream_t s);
