@@ -7,6 +7,7 @@
   mfma_chains        cycles per MFMA when 1..8 accumulators are updated round-robin (dependent-issue cost)
   lds_bandwidth      ds_read_b128 / ds_read_b64 / ds_read_b64_tr_b16 bytes per clock per CU
   lds_patterns       ds_read_b128 rate of the kernels' swizzled tile layout against other layouts
+  mfma_valu_overlap  whether vector-ALU instructions run in the shadow of MFMAs, in one wave and across two waves of a SIMD
   loop_ingredients   MFMA rate of the attention inner-loop skeleton as LDS operands, softmax ALU work
                      and the barrier are added one by one
 They were used to choose the LDS layout and to bound what the kernel structure can reach.
