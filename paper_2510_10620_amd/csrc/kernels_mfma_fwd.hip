@@ -96,81 +96,85 @@ __device__ __forceinline__ void fwd_scores64(const FwdState<NQ>& st, const char*
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// Online softmax over the (up to) 64 keys of a tile and O^T += V^T P^T.  This is the only code that touches the
-// output accumulators: every kind of tile (fully visible, mask edge, half skipped) computes its scores on its own
-// path and joins here, so the accumulators never meet at a control-flow merge with different register assignments
-// (which costs a copy of all 64 of them, there and back, per tile).  on[kt]: the 32-key sub-tile is not skipped;
-// the scores of a skipped one are -inf.
+// Online softmax over the 64 keys of a tile and O^T += V^T P^T.  This is the only code that touches the output
+// accumulators: every kind of tile (fully visible, mask edge, half skipped) computes its scores on its own path and
+// joins here, so the accumulators never meet at a control-flow merge with different register assignments (which
+// costs a copy of all 64 of them, there and back, per tile).  There is no branch on which sub-tiles are active
+// either (a skipped one has scores -inf, so P = 0 and its MFMAs add nothing): one straight block, in which the P.V
+// MFMAs of the first 32 keys are issued between the exponentials of the second 32 (the scheduling groups below say
+// so; exponentials are their own instruction class there).  NQ = 1.
 template <int NQ>
-__device__ __forceinline__ void fwd_softmax_pv(FwdState<NQ>& st, f32x16 (&s)[2][NQ], bool on0, bool on1, const char* v_lds,
-                                               float c_log2) {
-  bf16x8 p[2][NQ][2];
-  // V^T fragments of the first 16 keys that will be used, requested before the exponentials, which hide their latency
+__device__ __forceinline__ void fwd_softmax_pv(FwdState<NQ>& st, f32x16 (&s)[2][NQ], const char* v_lds, float c_log2) {
+  static_assert(NQ == 1, "one query per lane");
   bf16x8 va[4];
-  {
-    const char* v_first = v_lds + (on0 ? 0 : 32 * kRowBytes);
 #pragma unroll
-    for (int dt = 0; dt < 4; dt++) va[dt] = frag_tr(v_first, st.fa, 0, dt);
+  for (int dt = 0; dt < 4; dt++) va[dt] = frag_tr(v_lds, st.fa, 0, dt);
+  __builtin_amdgcn_sched_barrier(0);
+  float mx = fmaxf(fmaxf(s[0][0][0], s[0][0][1]), s[1][0][0]);
+  mx = fmaxf(mx, s[1][0][1]);
+#pragma unroll
+  for (int r = 2; r < 16; r += 2) {
+    mx = fmaxf(fmaxf(mx, s[0][0][r]), s[0][0][r + 1]);
+    mx = fmaxf(fmaxf(mx, s[1][0][r]), s[1][0][r + 1]);
+  }
+  mx = xhalf_max(mx);
+  // the reference max is raised lazily (see fwd_subtile); a row that has seen no key yet keeps m = -inf and uses 0
+  const bool raise = (mx - st.m[0]) * c_log2 > kLazy;
+  const float m_new = raise ? mx : st.m[0];
+  const float m_use = m_new == -INFINITY ? 0.f : m_new;
+  const float mc = m_use * c_log2;
+  if (__any(raise)) {
+    const float alpha = raise ? __builtin_amdgcn_exp2f((st.m[0] - m_use) * c_log2) : 1.f;
+    st.l[0] *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) st.o[0][dt][r] *= alpha;
+  }
+  st.m[0] = m_new;
+  // first 32 keys
+  float sum0 = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    const float e = __builtin_amdgcn_exp2f(fmaf(s[0][0][r], c_log2, -mc));
+    s[0][0][r] = e;
+    sum0 += e;
+  }
+  const bf16x8 p00 = pack_frag(s[0][0], 0), p01 = pack_frag(s[0][0], 1);
+  __builtin_amdgcn_sched_barrier(0);
+  // region: 8 MFMAs of the first 32 keys + the exponentials of the second 32, interleaved by the group barriers below
+  bf16x8 vb[4], vc[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++) vb[dt] = frag_tr(v_lds, st.fa, 16, dt);
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++) st.o[0][dt] = mfma(va[dt], p00, st.o[0][dt]);
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++) vc[dt] = frag_tr(v_lds, st.fa, 32, dt);
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++) st.o[0][dt] = mfma(vb[dt], p01, st.o[0][dt]);
+  float sum1 = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    const float e = __builtin_amdgcn_exp2f(fmaf(s[1][0][r], c_log2, -mc));
+    s[1][0][r] = e;
+    sum1 += e;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads for the MFMAs to come
+    __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // two exponentials
+    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // their multiply-adds and the running sum
   }
   __builtin_amdgcn_sched_barrier(0);
+  st.l[0] += sum0 + sum1;
+  const bf16x8 p10 = pack_frag(s[1][0], 0), p11 = pack_frag(s[1][0], 1);
 #pragma unroll
-  for (int nq = 0; nq < NQ; nq++) {
-    float mx = fmaxf(fmaxf(s[0][nq][0], s[0][nq][1]), s[1][nq][0]);
-    mx = fmaxf(mx, s[1][nq][1]);
+  for (int dt = 0; dt < 4; dt++) vb[dt] = frag_tr(v_lds, st.fa, 48, dt);
 #pragma unroll
-    for (int r = 2; r < 16; r += 2) {
-      mx = fmaxf(fmaxf(mx, s[0][nq][r]), s[0][nq][r + 1]);
-      mx = fmaxf(fmaxf(mx, s[1][nq][r]), s[1][nq][r + 1]);
-    }
-    mx = xhalf_max(mx);
-    // The reference max m is raised only when the tile's max exceeds it by more than 2^kLazy
-    // (in the exp2 domain): until then P = exp2(c (s - m)) stays below 2^kLazy, exact in fp32 and
-    // bf16 range, and the accumulators need no rescaling.  O and l are divided by the same sum at
-    // the end, so the result does not depend on which m was used.
-    const bool raise = (mx - st.m[nq]) * c_log2 > kLazy;   // also true for the first visible key (m = -inf)
-    const float m_new = raise ? mx : st.m[nq];
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row that has seen no key yet
-    const float mc = m_use * c_log2;
-    if (__any(raise)) {
-      const float alpha = raise ? __builtin_amdgcn_exp2f((st.m[nq] - m_use) * c_log2) : 1.f;
-      st.l[nq] *= alpha;
+  for (int dt = 0; dt < 4; dt++) st.o[0][dt] = mfma(vc[dt], p10, st.o[0][dt]);
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) st.o[nq][dt][r] *= alpha;
-    }
-    st.m[nq] = m_new;
-#pragma unroll
-    for (int kt = 0; kt < 2; kt++) {
-      if (!(kt ? on1 : on0)) continue;
-      float sum = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const float e = __builtin_amdgcn_exp2f(fmaf(s[kt][nq][r], c_log2, -mc));
-        s[kt][nq][r] = e;
-        sum += e;
-      }
-      st.l[nq] += sum;
-#pragma unroll
-      for (int c = 0; c < 2; c++) p[kt][nq][c] = pack_frag(s[kt][nq], c);
-    }
-  }
-#pragma unroll
-  for (int kt = 0; kt < 2; kt++) {
-    if (!(kt ? on1 : on0)) continue;
-    if (kt == 1 && on0) {   // va held sub-tile 0's fragments (only loads inside this branch, no accumulator)
-#pragma unroll
-      for (int dt = 0; dt < 4; dt++) va[dt] = frag_tr(v_lds, st.fa, 32, dt);
-    }
-#pragma unroll
-    for (int c = 0; c < 2; c++)
-#pragma unroll
-      for (int dt = 0; dt < 4; dt++) {
-        const bf16x8 a = c == 0 ? va[dt] : frag_tr(v_lds, st.fa, 32 * kt + 16, dt);
-#pragma unroll
-        for (int nq = 0; nq < NQ; nq++) st.o[nq][dt] = mfma(a, p[kt][nq][c], st.o[nq][dt]);
-      }
-  }
+  for (int dt = 0; dt < 4; dt++) st.o[0][dt] = mfma(vb[dt], p11, st.o[0][dt]);
 }
 
 // One 32-key sub-tile: S^T = K Q^T, mask, online softmax, O^T += V^T P^T.
@@ -458,7 +462,7 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
             }
           }
         }
-        fwd_softmax_pv<NQ>(st, s, cls0 != kSkip, cls1 != kSkip, cur + kTileBytes, c_log2);
+        fwd_softmax_pv<NQ>(st, s, cur + kTileBytes, c_log2);
       }
     }
     DCP_WAIT_VMCNT(0);
