@@ -7,6 +7,7 @@
 #include <cstring>
 #include <memory>
 #include <numeric>
+#include <queue>
 #include <set>
 
 #include "dcp_internal.h"
@@ -589,41 +590,71 @@ const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
   }
   HostItems hi;
   if (split_heads > 0) {
-    // An item longer than a quarter of a resident workgroup's share of the whole launch is cut, along its table
-    // rows, into parts of about that length: the tail of the launch is then a fraction of its body whatever the
-    // longest item was (one key tile under a sink or one query tile that sees everything can otherwise outlast
-    // the rest of the grid).  Parts hold whole table rows, at most kMaxParts of them per item.
-    const int64_t limit = std::max<int64_t>(1, total * split_heads / kResidentWorkgroups / 4);
-    std::vector<Scored> cut;
-    for (const Scored& it : sc) {
-      const int32_t n_ent = it.w.e1 - it.w.e0;
-      int64_t want = (it.cost + limit - 1) / limit;
-      const int32_t n_parts = (int32_t)std::min<int64_t>(std::min<int64_t>(want, n_ent), kMaxParts);
-      if (n_parts <= 1) { cut.push_back(it); continue; }
-      const WorkItem& w = it.w;
-      int64_t r0 = blk_start[hg->unit_blk[w.unit]] + (int64_t)w.tile * tile_rows;
-      int64_t r1 = std::min<int64_t>(r0 + tile_rows, blk_start[hg->unit_blk[w.unit]] + blk_len[hg->unit_blk[w.unit]]);
-      ecost.assign(n_ent, 0);
-      for (int32_t e = w.e0; e < w.e1; e++)
-        ecost[e - w.e0] = tile_cost(hg->ent_kind[e], r0, r1, hg->ent_start[e], hg->ent_start[e] + hg->ent_len[e], gid == 2);
-      // contiguous chunks of table rows of about cost / n_parts each, every chunk non-empty
-      hi.reduce.push_back({w.unit, w.tile, hi.n_pslots, n_parts});
-      int32_t e = w.e0;
-      int64_t done = 0;
-      for (int32_t p = 0; p < n_parts; p++) {
-        const int32_t left_parts = n_parts - p - 1;
-        const int64_t goal = it.cost * (p + 1) / n_parts;
-        int32_t e_hi = e + 1;
-        int64_t c = ecost[e - w.e0];
-        while (e_hi < w.e1 - left_parts && done + c < goal) { c += ecost[e_hi - w.e0]; e_hi++; }
-        if (p == n_parts - 1) { while (e_hi < w.e1) { c += ecost[e_hi - w.e0]; e_hi++; } }
-        cut.push_back({{w.unit, w.tile, e, e_hi, hi.n_pslots + p, {0, 0, 0}}, c});
-        done += c;
-        e = e_hi;
+    // Long items are cut, along their table rows, into parts (each with a slot of fp32 partial sums that a reduce
+    // kernel adds up): one key tile under a sink, or the first keys of the one long sequence of a small batch, can
+    // otherwise outlast the rest of the grid.  Cutting costs partial-sum traffic and a second start-up per part
+    // (measured on the 65 536-token causal batch: every doubling of the number of parts beyond need costs 2-5 % of
+    // the kernel), so the least cutting that balances the launch is chosen: the launch is played through as list
+    // scheduling (items in the order they are issued, longest first, each on the workgroup slot that frees up
+    // first) and items longer than 1/d of a slot's share are cut for d = 0 (none), 1, 2, 4 until the estimated
+    // finish is within 5 % of the share, or d = 4 is reached.  Parts hold whole table rows, at most kMaxParts.
+    const double share = (double)total * split_heads / kResidentWorkgroups;
+    auto finish_time = [&](std::vector<Scored> v) {
+      std::stable_sort(v.begin(), v.end(), [](const Scored& a, const Scored& b) { return a.cost > b.cost; });
+      std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> slots;
+      for (int64_t i = 0; i < kResidentWorkgroups; i++) slots.push(0);
+      int64_t end = 0;
+      for (int h = 0; h < split_heads; h++)          // the grid runs the list once per head, head-major
+        for (const Scored& it : v) {
+          int64_t t0 = slots.top();
+          slots.pop();
+          slots.push(t0 + it.cost);
+          end = std::max(end, t0 + it.cost);
+        }
+      return (double)end;
+    };
+    auto cut_at = [&](int64_t limit, HostItems* out) {
+      std::vector<Scored> cut;
+      out->reduce.clear();
+      out->n_pslots = 0;
+      for (const Scored& it : sc) {
+        const int32_t n_ent = it.w.e1 - it.w.e0;
+        int64_t want = (it.cost + limit - 1) / limit;
+        const int32_t n_parts = (int32_t)std::min<int64_t>(std::min<int64_t>(want, n_ent), kMaxParts);
+        if (n_parts <= 1) { cut.push_back(it); continue; }
+        const WorkItem& w = it.w;
+        int64_t r0 = blk_start[hg->unit_blk[w.unit]] + (int64_t)w.tile * tile_rows;
+        int64_t r1 = std::min<int64_t>(r0 + tile_rows, blk_start[hg->unit_blk[w.unit]] + blk_len[hg->unit_blk[w.unit]]);
+        ecost.assign(n_ent, 0);
+        for (int32_t e = w.e0; e < w.e1; e++)
+          ecost[e - w.e0] = tile_cost(hg->ent_kind[e], r0, r1, hg->ent_start[e], hg->ent_start[e] + hg->ent_len[e], gid == 2);
+        // contiguous chunks of table rows of about cost / n_parts each, every chunk non-empty
+        out->reduce.push_back({w.unit, w.tile, out->n_pslots, n_parts});
+        int32_t e = w.e0;
+        int64_t done = 0;
+        for (int32_t p = 0; p < n_parts; p++) {
+          const int32_t left_parts = n_parts - p - 1;
+          const int64_t goal = it.cost * (p + 1) / n_parts;
+          int32_t e_hi = e + 1;
+          int64_t c = ecost[e - w.e0];
+          while (e_hi < w.e1 - left_parts && done + c < goal) { c += ecost[e_hi - w.e0]; e_hi++; }
+          if (p == n_parts - 1) { while (e_hi < w.e1) { c += ecost[e_hi - w.e0]; e_hi++; } }
+          cut.push_back({{w.unit, w.tile, e, e_hi, out->n_pslots + p, {0, 0, 0}}, c});
+          done += c;
+          e = e_hi;
+        }
+        out->n_pslots += n_parts;
       }
-      hi.n_pslots += n_parts;
+      return cut;
+    };
+    if (total > 0 && finish_time(sc) > 1.05 * share) {
+      std::vector<Scored> best;
+      for (int d = 1; d <= 4; d *= 2) {
+        best = cut_at(std::max<int64_t>(1, (int64_t)(share / d)), &hi);
+        if (finish_time(best) <= 1.05 * std::max(share, 1.0)) break;
+      }
+      sc.swap(best);
     }
-    sc.swap(cut);
   }
   std::stable_sort(sc.begin(), sc.end(), [](const Scored& a, const Scored& b) { return a.cost > b.cost; });
   hi.items.resize(sc.size());

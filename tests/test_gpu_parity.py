@@ -46,7 +46,12 @@ SPECS = [W.MaskSpec("causal"), W.MaskSpec("window", window=200), W.MaskSpec("lam
 def test_small_bf16_all_masks(spec, impl):
     w = W.custom_workload("small", [300, 77, 1000, 1, 130], 128, 4, 2, 128, "bf16", spec, seed=31, input_scale=0.5)
     table = H.oracle_table(w)
-    run_case(w, table, IMPLS[impl], label=f"{spec.kind}/{impl}")
+    g, _, _ = run_case(w, table, IMPLS[impl], label=f"{spec.kind}/{impl}")
+    if impl == "auto":
+        # the 1000-token sequence's key tiles are long items for so small a launch: the run above went through split
+        # dK/dV items, their fp32 partial sums and the reduce kernel
+        import paper_2510_10620_amd as P
+        assert (P.dcp_plan_export_dkv_items(g.plan, w.hkv)[:, 4] >= 0).any()
 
 
 @pytest.mark.parametrize("impl", list(IMPLS), ids=list(IMPLS))
