@@ -8,6 +8,7 @@
   lds_bandwidth      ds_read_b128 / ds_read_b64 / ds_read_b64_tr_b16 bytes per clock per CU
   lds_patterns       ds_read_b128 rate of the kernels' swizzled tile layout against other layouts
   mfma_valu_overlap  whether vector-ALU instructions run in the shadow of MFMAs, in one wave and across two waves of a SIMD
+  hbm_stream         GB/s of plain read-only, write-only and copy kernels (what the HBM-bound kernels can be held against)
   loop_ingredients   MFMA rate of the attention inner-loop skeleton as LDS operands, softmax ALU work
                      and the barrier are added one by one
 They were used to choose the LDS layout and to bound what the kernel structure can reach.
