@@ -251,84 +251,12 @@ __device__ __forceinline__ void fwd_subtile(FwdState<NQ>& st, const char* k_lds,
     }
 }
 
-// A whole 64-key tile every pair of which is visible to the wave: the two 32-key score tiles are
-// two independent MFMA chains, and the max / rescale bookkeeping is done once for 64 keys.
+// A whole 64-key tile every pair of which is visible to the wave (kernel variant for tables with per-token ranges).
 template <int NQ>
 __device__ __forceinline__ void fwd_tile64(FwdState<NQ>& st, const char* k_lds, const char* v_lds, float c_log2) {
   f32x16 s[2][NQ];
-#pragma unroll
-  for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-    for (int nq = 0; nq < NQ; nq++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) s[kt][nq][r] = 0.f;
-  // K fragments are requested four k-steps ahead of the MFMAs that use them
-  constexpr int PF = 4;
-  bf16x8 ka[8][2];
-#pragma unroll
-  for (int ksd = 0; ksd < PF; ksd++)
-#pragma unroll
-    for (int kt = 0; kt < 2; kt++) ka[ksd][kt] = frag_rm(k_lds, st.fa, 32 * kt, ksd);
-#pragma unroll
-  for (int ksd = 0; ksd < 8; ksd++) {
-    __builtin_amdgcn_sched_barrier(0);
-    if (ksd + PF < 8) {
-#pragma unroll
-      for (int kt = 0; kt < 2; kt++) ka[ksd + PF][kt] = frag_rm(k_lds, st.fa, 32 * kt, ksd + PF);
-    }
-#pragma unroll
-    for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-      for (int nq = 0; nq < NQ; nq++) s[kt][nq] = mfma(ka[ksd][kt], st.qf[nq][ksd], s[kt][nq]);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  bf16x8 p[2][NQ][2];
-#pragma unroll
-  for (int nq = 0; nq < NQ; nq++) {
-    float mx = fmaxf(fmaxf(s[0][nq][0], s[0][nq][1]), s[1][nq][0]);
-    mx = fmaxf(mx, s[1][nq][1]);
-#pragma unroll
-    for (int r = 2; r < 16; r += 2) {
-      mx = fmaxf(fmaxf(mx, s[0][nq][r]), s[0][nq][r + 1]);
-      mx = fmaxf(fmaxf(mx, s[1][nq][r]), s[1][nq][r + 1]);
-    }
-    mx = xhalf_max(mx);
-    const bool raise = (mx - st.m[nq]) * c_log2 > kLazy;
-    const float m_new = raise ? mx : st.m[nq];
-    const float mc = m_new * c_log2;               // finite: a full tile has a finite max
-    if (__any(raise)) {
-      const float alpha = raise ? __builtin_amdgcn_exp2f((st.m[nq] - m_new) * c_log2) : 1.f;
-      st.l[nq] *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) st.o[nq][dt][r] *= alpha;
-    }
-    st.m[nq] = m_new;
-    float sum0 = 0.f, sum1 = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const float e0 = __builtin_amdgcn_exp2f(fmaf(s[0][nq][r], c_log2, -mc));
-      const float e1 = __builtin_amdgcn_exp2f(fmaf(s[1][nq][r], c_log2, -mc));
-      s[0][nq][r] = e0; s[1][nq][r] = e1;
-      sum0 += e0; sum1 += e1;
-    }
-    st.l[nq] += sum0 + sum1;
-#pragma unroll
-    for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-      for (int c = 0; c < 2; c++) p[kt][nq][c] = pack_frag(s[kt][nq], c);
-  }
-#pragma unroll
-  for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-    for (int c = 0; c < 2; c++)
-#pragma unroll
-      for (int dt = 0; dt < 4; dt++) {
-        const bf16x8 a = frag_tr(v_lds, st.fa, 32 * kt + 16 * c, dt);
-#pragma unroll
-        for (int nq = 0; nq < NQ; nq++) st.o[nq][dt] = mfma(a, p[kt][nq][c], st.o[nq][dt]);
-      }
+  fwd_scores64<NQ>(st, k_lds, s);
+  fwd_softmax_pv<NQ>(st, s, v_lds, c_log2);
 }
 
 // RANGES = false: the table has no row with per-token ranges (RANGES or WINDOW) and every use of them folds away.
