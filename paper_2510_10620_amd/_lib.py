@@ -89,6 +89,10 @@ def load():
     if not os.path.exists(LIB_PATH):
         from . import build as _build
         _build.build(verbose=False)
+    # torch first: it brings its own copy of the HIP runtime, and the device tensors this binding is handed live in
+    # that copy.  Loaded after torch, the library binds to the same runtime; loaded before it, the process would hold
+    # two runtimes and the library's own would find no device ("no ROCm-capable device is detected").
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     for name, (res, args) in _SIGS.items():
         fn = getattr(lib, name)          # AttributeError if the symbol is not exported

@@ -78,6 +78,38 @@ def test_window_kind_rows_need_no_range_array(window, sink, impl):
             by_row=(window == 1))
 
 
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (8, 1), (6, 2)])
+def test_head_group_sizes(hq, hkv):
+    """Query heads per KV head other than the benchmark's 4: 1 (no sharing), 8 and 3 (not a power of two)."""
+    w = W.custom_workload("groups", [333, 200], 128, hq, hkv, 128, "bf16", W.MaskSpec("lambda", window=90, sink=9), seed=35,
+                          input_scale=0.5)
+    run_case(w, H.oracle_table(w), IMPLS["auto"], label=f"hq{hq}/hkv{hkv}")
+
+
+def test_library_loaded_before_torch_touches_the_gpu():
+    """A fresh process that calls a host function of the binding (which loads the library) before anything has
+    imported torch must still find the GPU afterwards: the loader imports torch first so that the process holds one
+    HIP runtime.  One child process, one small forward."""
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2510_10620_amd as P\n"
+        "from paper_2510_10620_amd import workloads as W\n"
+        "w = W.custom_workload('x', [300], 128, 4, 2, 128, 'bf16', W.MaskSpec('causal'), seed=1, input_scale=0.5)\n"
+        "table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)\n"
+        "import torch\n"
+        "q = torch.randn((300, 4, 128), device='cuda').to(torch.bfloat16); k = torch.randn((300, 2, 128), device='cuda').to(torch.bfloat16)\n"
+        "out = torch.empty_like(q); lse = torch.empty((4, 300), dtype=torch.float32, device='cuda')\n"
+        "plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)\n"
+        "P.dcp_block_attn_fwd(plan, q, k, k, out, lse, w.softmax_scale, None)\n"
+        "torch.cuda.synchronize(); assert bool(torch.isfinite(out.float()).all()); print('ok')\n"
+    ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
+
+
 def test_window_rows_without_parameters_are_refused():
     import paper_2510_10620_amd as P
     spec = W.MaskSpec("window", window=40)
