@@ -221,7 +221,8 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
   }
 }
 
-// RANGES = false: the table has no RANGES row; everything that serves them is compiled out.
+// RANGES = false: the table has no row with per-token ranges (RANGES or WINDOW); everything that serves them is
+// compiled out.  Two workgroups per CU: at most 256 registers.
 template <bool RANGES>
 __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t) {
   constexpr int TK = 128;
