@@ -215,6 +215,21 @@ def test_edge_cases(impl):
     assert ei.value.status in (P.DCP_ERR_UNSUPPORTED, P.DCP_ERR_INVALID_ARG)
 
 
+@pytest.mark.parametrize("B", [32, 96, 4096])
+def test_block_sizes_off_the_tile_grid(B):
+    """Block sizes below the kernels' 128-row / 64-key tiles, not a multiple of them, and larger than every
+    sequence, with the lambda mask and with the WINDOW kind on top of block buffers and partial slots."""
+    import paper_2510_10620_amd as P
+    spec = W.MaskSpec("lambda", window=70, sink=11)
+    w = W.custom_workload("blocks", [333, 97, 500], B, 4, 2, 128, "bf16", spec, seed=36, input_scale=0.5)
+    run_case(w, H.oracle_table(w), IMPLS["auto"], label=f"B{B}")
+    # the same mask as WINDOW rows, through block buffers with permuted slots and divisions into partial slots
+    table = P.dcp_build_block_table_window(w.cu_seqlens, w.block_size, 70, 11)
+    rng = np.random.default_rng(B)
+    slot, n_slots, _ = W.deal_divisions(table[:, 0], 2, 5)
+    _buffer_case(w, table, IMPLS["auto"], rng, out_slot=slot, n_slots=n_slots, window=(70, 11))
+
+
 def test_strided_inputs_fused_qkv_layout():
     """q, k, v as views of one [T, (Hq + 2 Hkv) * D] projection output."""
     import torch
@@ -301,7 +316,7 @@ def test_blockwise_copy_bit_exact():
     P.dcp_blockwise_copy(P.CopyList(np.zeros((0, 3), np.int32), T, n_slots * B), tx, tbuf)
 
 
-def _buffer_case(w, table, impl, rng, absent_ok=False, out_slot=None, n_slots=0):
+def _buffer_case(w, table, impl, rng, absent_ok=False, out_slot=None, n_slots=0, window=None):
     """Runs forward + backward with every tensor held in block buffers (permuted slots, free slots in
     between, unused rows poisoned) and compares what comes back, block by block, with the oracle on the
     packed tensors.  Returns nothing; asserts."""
@@ -325,12 +340,14 @@ def _buffer_case(w, table, impl, rng, absent_ok=False, out_slot=None, n_slots=0)
         kv_slot[~used_kv] = -1
     plan = P.dcp_plan_create(w.cu_seqlens, B, table, out_slot, n_slots)
     P.dcp_plan_set_block_buffers(plan, q_slot, n_qs, kv_slot, n_ks)
+    if window is not None:            # WINDOW rows: two numbers, no range array
+        P.dcp_plan_set_window(plan, *window)
     nan16 = np.uint16(0x7FC0)
     fill = nan16 if w.dtype == "bf16" else np.float32("nan")
     buf = {n: BB.gather_blocks(tensors[n], bs, bl, q_slot if n in ("q", "dout") else kv_slot,
                                n_qs if n in ("q", "dout") else n_ks, B, fill=fill) for n in ("q", "k", "v", "dout")}
     tq, tk, tv, tdo = (H.to_torch(w, buf[n]) for n in ("q", "k", "v", "dout"))
-    rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+    rg = None if window is not None else torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
     out = torch.full((n_qs * B, w.hq, w.d), 768.0, dtype=tq.dtype, device="cuda")
     lse = torch.full((w.hq, n_qs * B), 768.0, dtype=torch.float32, device="cuda")
     if out_slot is not None:
@@ -345,7 +362,7 @@ def _buffer_case(w, table, impl, rng, absent_ok=False, out_slot=None, n_slots=0)
     dv = torch.full_like(dk, 768.0)
     ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plan, w.hq, w.hkv, w.d, P.DCP_BF16 if w.dtype == "bf16" else P.DCP_F32)),
                      dtype=torch.uint8, device="cuda")
-    ref = H.oracle_full(w, tensors, table)
+    ref = H.oracle_full(w, tensors, table, window=window)
     # the backward takes the forward's out / lse when the table is complete; for a share, the oracle's global ones
     P.dcp_block_attn_bwd(plan, tq, tk, tv, out, lse, tdo, dq, dk, dv, w.softmax_scale, ws, rg, impl)
     torch.cuda.synchronize()
