@@ -201,8 +201,14 @@ def make_workload(cfg: int, tokens: Optional[int] = None) -> Workload:
         lens = draw_lengths(T, "lognormal", 1024, 65536, seed=7, median=8192)
         w = Workload("shared_question_bf16", cu_from_lengths(lens), 1024, 32, 8, 128, "bf16",
                      MaskSpec("shared_question", n_answers=4, frac=0.2), 107, 1.0 / math.sqrt(128))
+    elif cfg == 8:
+        # the longest sequence of the paper's evaluation (maximum sequence length 131 072, Sec. 7.1) as one causal
+        # sequence, with a five-token sequence beside it so that the long one ends in a ragged block
+        T = tokens or 131072
+        w = Workload("one_long_sequence_bf16", cu_from_lengths([T - 5, 5]), 1024, 32, 8, 128, "bf16",
+                     MaskSpec("causal"), 108, 1.0 / math.sqrt(128))
     else:
-        raise ValueError(f"config {cfg} not in 1..7")
+        raise ValueError(f"config {cfg} not in 1..8")
     w.softmax_scale = 1.0 / math.sqrt(w.d)
     w.ranges = attn_ranges(w.mask, w.cu_seqlens)
     return w

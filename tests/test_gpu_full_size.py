@@ -1,5 +1,5 @@
-"""Parity at the benchmark's full sizes and launch configuration (configs 2-5, and the two remaining mask
-families of the paper at the same scale, 6-7): the HIP path on the
+"""Parity at the benchmark's full sizes and launch configuration (configs 2-5, the two remaining mask
+families of the paper at the same scale, 6-7, and one causal sequence of the paper's maximum length, 8): the HIP path on the
 whole batch, checked (a) against the fp64 oracle on sampled query-row windows (complete O, LSE and
 dQ for the window's rows; complete dK / dV for the keys only the window sees) and (b) on EVERY
 element against a linear-time closed form: with Q = 0 the softmax is uniform over the visible set,
@@ -90,7 +90,7 @@ def _windows(w):
     return [(n, s, int(a), int(b)) for n, s, a, b in probes]
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 6, 7, 8])
 def test_full_size_config(cfg):
     import torch
     import paper_2510_10620_amd as P
