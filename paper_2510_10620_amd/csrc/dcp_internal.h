@@ -32,7 +32,9 @@ struct WorkItem {
   int32_t tile;
   int32_t e0, e1;
   int32_t pslot;
-  int32_t pad[3];
+  // the unit's own block, so that a workgroup needs one load, not a chain of them, before it can address its rows:
+  int32_t blk_start, blk_len;   // first packed token and length
+  int32_t moff;                 // memory row = packed index + moff (block buffers; 0 for packed tensors)
 };
 
 // A split (unit, tile): the parts' slots are first_pslot .. first_pslot + n_parts - 1, summed in that order.

@@ -64,12 +64,11 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   if (!decode_wg(g.n_items, t.hkv, G, &item, &head)) return;
   const int hk = head / G;
   WorkItem w = g.items[item];
-  w.unit = uni(w.unit); w.tile = uni(w.tile);
-  const int qb = uni(g.unit_blk[w.unit]);
+  w.unit = uni(w.unit); w.tile = uni(w.tile); w.e0 = uni(w.e0); w.e1 = uni(w.e1);
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
-  const int blk_start = uni(g.blk_start[qb]), blk_len = uni(g.blk_len[qb]);
-  const int qoff = uni(g.unit_moff[w.unit]);   // rows of the Q-type buffers: packed index + qoff
+  const int blk_start = uni(w.blk_start), blk_len = uni(w.blk_len);
+  const int qoff = uni(w.moff);                // rows of the Q-type buffers: packed index + qoff
   const int row0 = w.tile * TM;
   const int n_rows = min(TM, blk_len - row0);
   const int q_lo = blk_start + row0, q_hi = q_lo + n_rows - 1;
@@ -88,7 +87,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   RangeBounds wrb;
   wrb.init();
   if (t.masked) {
-    st.qr = range_row(t, st.qi, uni(g.blk_s0[qb]));
+    st.qr = range_row(t, st.qi, uni(g.blk_s0[uni(g.unit_blk[w.unit])]));
     if (qv) wrb.add(st.qr);
   }
   RangeBounds rb = wrb;
@@ -131,7 +130,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   const bf16_t* kbase = (const bf16_t*)t.k + (int64_t)hk * t.k_sh;
   const bf16_t* vbase = (const bf16_t*)t.v + (int64_t)hk * t.v_sh;
 
-  KvIter it(g, w.unit);
+  KvIter it(g, w.e0, w.e1);
   bool have = it.next<RANGES>(q_hi, rb);
   if (have) {
     st.dmak.load(stage0, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);

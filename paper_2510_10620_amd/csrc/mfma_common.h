@@ -292,8 +292,9 @@ struct KvIter {
   int c0, c1, kind;
   int moff;  // the KV block's rows sit at (packed index + moff) in the KV-type buffers
   int ks;    // first key of the current tile
-  __device__ KvIter(const DevGroup& g, int unit) : rec((const int4*)g.ent_rec) {
-    e = uni(g.ptr[unit]) - 1; e_end = uni(g.ptr[unit + 1]); jt = 0; n_t = 0; c0 = c1 = kind = 0; moff = 0; ks = 0;
+  // [e0, e1): the unit's table rows (from the work item)
+  __device__ KvIter(const DevGroup& g, int e0, int e1) : rec((const int4*)g.ent_rec) {
+    e = e0 - 1; e_end = e1; jt = 0; n_t = 0; c0 = c1 = kind = 0; moff = 0; ks = 0;
   }
   // Advances to the next tile some row of [.., q_hi] may see; false when the unit is done.
   // RANGES = false: the table has no RANGES row (nothing of the range machinery is compiled in).

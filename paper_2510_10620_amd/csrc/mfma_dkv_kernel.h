@@ -233,12 +233,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
   const int G = t.hq / t.hkv;
   WorkItem w = g.items[item];
   w.unit = uni(w.unit); w.tile = uni(w.tile); w.e0 = uni(w.e0); w.e1 = uni(w.e1); w.pslot = uni(w.pslot);
-  const int kb = uni(g.unit_blk[w.unit]);
+
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
-  const int blk_start = uni(g.blk_start[kb]), blk_len = uni(g.blk_len[kb]);
-  const int koff = uni(g.unit_moff[w.unit]);   // rows of the KV-type buffers: packed index + koff
-  const int seq0 = RANGES ? uni(g.blk_s0[kb]) : 0;   // first token of the sequence (keys and queries share it)
+  const int blk_start = uni(w.blk_start), blk_len = uni(w.blk_len);
+  const int koff = uni(w.moff);   // rows of the KV-type buffers: packed index + koff
+  const int seq0 = RANGES ? uni(g.blk_s0[uni(g.unit_blk[w.unit])]) : 0;   // first token of the sequence (keys and queries share it)
   const int row0 = w.tile * TK;
   const int n_rows = min(TK, blk_len - row0);
   const int k_lo = blk_start + row0, k_end = k_lo + n_rows;

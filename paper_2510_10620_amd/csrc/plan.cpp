@@ -584,7 +584,7 @@ const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
       int64_t cost = 0;
       for (int32_t e = hg->ptr[u]; e < hg->ptr[u + 1]; e++)
         cost += tile_cost(hg->ent_kind[e], r0, r1, hg->ent_start[e], hg->ent_start[e] + hg->ent_len[e], gid == 2);
-      sc.push_back({{u, t, hg->ptr[u], hg->ptr[u + 1], -1, {0, 0, 0}}, cost});
+      sc.push_back({{u, t, hg->ptr[u], hg->ptr[u + 1], -1, blk_start[b], blk_len[b], (gid == 2 ? kv_moff : q_moff)[b]}, cost});
       total += cost;
     }
   }
@@ -639,7 +639,7 @@ const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
           int64_t c = ecost[e - w.e0];
           while (e_hi < w.e1 - left_parts && done + c < goal) { c += ecost[e_hi - w.e0]; e_hi++; }
           if (p == n_parts - 1) { while (e_hi < w.e1) { c += ecost[e_hi - w.e0]; e_hi++; } }
-          cut.push_back({{w.unit, w.tile, e, e_hi, out->n_pslots + p, {0, 0, 0}}, c});
+          cut.push_back({{w.unit, w.tile, e, e_hi, out->n_pslots + p, w.blk_start, w.blk_len, w.moff}, c});
           done += c;
           e = e_hi;
         }
