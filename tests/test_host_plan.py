@@ -185,6 +185,53 @@ def test_window_kind_error_paths():
     assert _status(P.dcp_count_pairs, cu, 64, t_win) == P.DCP_ERR_BAD_TABLE      # WINDOW rows need the window counter
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_plans_groupings_and_work_lists(seed):
+    """Random lengths, block sizes, mask families, row orders, SKIP rows and head counts: the CSR groupings equal the
+    oracle's, and the dK/dV work list is an exact partition of every (kv_blk, tile)'s table rows whatever gets cut."""
+    rng = np.random.default_rng(1000 + seed)
+    lens = [int(x) for x in rng.integers(1, 900, size=int(rng.integers(1, 7)))]
+    B = int(rng.choice([16, 48, 128, 256]))
+    spec = [W.MaskSpec("causal"), W.MaskSpec("window", window=int(rng.integers(1, 300))),
+            W.MaskSpec("lambda", window=int(rng.integers(1, 200)), sink=int(rng.integers(1, 40))),
+            W.MaskSpec("causal_blockwise", window=2, sink=1, mblock=int(rng.choice([8, 32, 96]))),
+            W.MaskSpec("shared_question")][seed % 5]
+    cu = W.cu_from_lengths(lens)
+    table = _oracle_table(spec, cu, B)
+    table = table[rng.permutation(len(table))]
+    if len(table) > 3:
+        table[rng.choice(len(table), size=len(table) // 5, replace=False), 2] = W.MASK_SKIP
+    nb = len(OB.block_partition(cu, B)["blk_seq"])
+    plan = P.dcp_plan_create(cu, B, table)
+    for col, ptr_name, idx_name in ((0, "FWD_PTR", "FWD_IDX"), (0, "BWDQ_PTR", "BWDQ_IDX"), (1, "BWDKV_PTR", "BWDKV_IDX")):
+        ptr, idx = OB.group_entries(table, col, nb)
+        assert np.array_equal(plan.export(ptr_name), ptr), ptr_name
+        assert np.array_equal(plan.export(idx_name), idx), idx_name
+    hkv = int(rng.choice([1, 2, 8]))
+    items = P.dcp_plan_export_dkv_items(plan, hkv)
+    ptr, blk_len = plan.export("BWDKV_PTR"), plan.export("BLK_LEN")
+    by_tile = {}
+    for u, t, e0, e1, ps in items.tolist():
+        by_tile.setdefault((u, t), []).append((e0, e1, ps))
+    # every tile of every block is there, also of blocks no kept row lists as kv_blk: their dK / dV rows get zeros
+    assert set(by_tile) == {(u, t) for u in range(nb) for t in range((blk_len[u] + 127) // 128)}
+    slots = []
+    for (u, t), parts in by_tile.items():
+        parts.sort()
+        assert parts[0][0] == ptr[u] and parts[-1][1] == ptr[u + 1]
+        assert all(a[1] == b[0] for a, b in zip(parts, parts[1:]))
+        assert all(e1 > e0 for e0, e1, _ in parts) or (len(parts) == 1 and ptr[u] == ptr[u + 1])
+        if len(parts) == 1:
+            assert parts[0][2] == -1
+        else:
+            ps = [p for _, _, p in parts]
+            assert ps == list(range(ps[0], ps[0] + len(ps)))
+            slots += ps
+    assert sorted(slots) == list(range(len(slots)))
+    assert P.dcp_bwd_workspace_bytes(plan, 4 * hkv, hkv, 128, P.DCP_BF16) - P.dcp_bwd_workspace_bytes(plan, 4 * hkv, hkv, 64, P.DCP_BF16) \
+        == len(slots) * hkv * 2 * 128 * 128 * 4
+
+
 def _status(fn, *a, **k):
     with pytest.raises(P.DcpError) as ei:
         fn(*a, **k)
