@@ -78,6 +78,28 @@ def test_window_kind_rows_need_no_range_array(window, sink, impl):
             by_row=(window == 1))
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_small_cases(seed):
+    """Random lengths (ragged, some below a tile), block size, head counts, mask family and table row order."""
+    rng = np.random.default_rng(2000 + seed)
+    lens = [int(x) for x in rng.integers(1, 700, size=int(rng.integers(1, 6)))]
+    B = int(rng.choice([32, 64, 128, 256]))
+    hq, hkv = [(4, 2), (8, 2), (4, 4)][seed % 3]
+    spec = [W.MaskSpec("causal"), W.MaskSpec("window", window=int(rng.integers(1, 300))),
+            W.MaskSpec("lambda", window=int(rng.integers(1, 200)), sink=int(rng.integers(1, 40))),
+            W.MaskSpec("causal_blockwise", window=2, sink=1, mblock=int(rng.choice([8, 32, 96]))),
+            W.MaskSpec("shared_question")][int(rng.integers(0, 5))]
+    w = W.custom_workload("random", lens, B, hq, hkv, 128, "bf16", spec, seed=40 + seed, input_scale=0.5)
+    table = H.oracle_table(w)
+    table = table[rng.permutation(len(table))]
+    tensors = W.make_tensors(w)
+    g = H.GpuRun(w, tensors, table, impl=IMPLS["auto"])
+    out, lse = g.forward()
+    dq, dk, dv = g.backward()
+    H.check(w, dict(out=out, lse=lse, dq=dq, dk=dk, dv=dv), H.oracle_full(w, tensors, table), ALL,
+            f"random {seed}: lens {lens} B {B} {hq}/{hkv} {spec.kind}")
+
+
 @pytest.mark.parametrize("hq,hkv", [(2, 2), (8, 1), (6, 2)])
 def test_head_group_sizes(hq, hkv):
     """Query heads per KV head other than the benchmark's 4: 1 (no sharing), 8 and 3 (not a power of two)."""
