@@ -100,6 +100,14 @@ def test_random_small_cases(seed):
             f"random {seed}: lens {lens} B {B} {hq}/{hkv} {spec.kind}")
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("bf16", 32), ("f32", 128), ("f32", 32)])
+def test_shapes_only_the_scalar_family_covers(dtype, d):
+    """dtype / head-dim pairs outside the MFMA family (bf16, D 128): AUTO must pick the scalar kernels and be right."""
+    w = W.custom_workload("scalar_shapes", [210, 75], 64, 4, 2, d, dtype, W.MaskSpec("lambda", window=60, sink=5), seed=37,
+                          input_scale=0.5)
+    run_case(w, H.oracle_table(w), IMPLS["auto"], label=f"{dtype}/D{d}")
+
+
 @pytest.mark.parametrize("hq,hkv", [(2, 2), (8, 1), (6, 2)])
 def test_head_group_sizes(hq, hkv):
     """Query heads per KV head other than the benchmark's 4: 1 (no sharing), 8 and 3 (not a power of two)."""
