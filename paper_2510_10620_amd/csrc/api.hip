@@ -243,7 +243,11 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
     k.qbounds = qb;
     if ((st = mfma_range_bounds(gkv, k, plan->d_blk_t32, plan->n_blocks, qb, s)) != DCP_OK) return st;
   }
-  {
+  if (use_mfma) {
+    // the MFMA dQ kernel computes delta and the rescaled LSE of its own rows and leaves them for the dK/dV kernel
+    k.delta_w = delta;
+    k.lse2_w = lse2;
+  } else {
     ProfScope ps(DCP_K_DELTA, s);
     if ((st = stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
                            t->lse, lse2, plan->q_rows, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;

@@ -9,6 +9,8 @@ struct KTensors {
   const void *q, *k, *v, *dout, *out_in;
   void *out, *dq, *dk, *dv;
   float* lse;              // forward: output; backward: input
+  float* delta_w;          // backward, MFMA family: where the dQ kernel leaves delta and lse2 (the same arrays as below) for
+  float* lse2_w;           //   the dK/dV kernel; null when a separate preprocess kernel has filled them
   const float* delta;      // backward input [Hq,T]
   const float* lse2;       // backward input [Hq,T]: max(lse * log2(e), -FLT_MAX), made by the preprocess
   const int32_t* ranges;   // [T,4] or null (tables without RANGES rows)

@@ -119,8 +119,34 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
       st.qf[ks] = as_frag(*(const uint4*)(qp + 16 * ks));
       st.dof[ks] = as_frag(*(const uint4*)(dop + 16 * ks));
     }
-    st.lse2 = t.lse2[(int64_t)head * t.q_rows + st.qi + qoff];
-    st.delta = t.delta[(int64_t)head * t.q_rows + st.qi + qoff];
+    if (t.delta_w) {
+      // the backward preprocess, fused: delta = sum_d dO * O of the lane's row from the final O, and the saved LSE in
+      // the exp2 domain (clamped to a finite value: a row that saw nothing has every score masked); both are left
+      // in the workspace for the dK/dV kernel, which runs after this one
+      const bf16_t* outp = (const bf16_t*)t.out_in + (int64_t)(st.qi + qoff) * t.o_st + (int64_t)head * t.o_sh + 8 * lh;
+      float dl = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++) {
+        const uint4 u = *(const uint4*)(outp + 16 * ks);
+        const uint32_t ow[4] = {u.x, u.y, u.z, u.w};
+        const uint4 dd = __builtin_bit_cast(uint4, st.dof[ks]);
+        const uint32_t dw[4] = {dd.x, dd.y, dd.z, dd.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          dl = fmaf(__uint_as_float(ow[i] << 16), __uint_as_float(dw[i] << 16), dl);
+          dl = fmaf(__uint_as_float(ow[i] & 0xffff0000u), __uint_as_float(dw[i] & 0xffff0000u), dl);
+        }
+      }
+      st.delta = xhalf_sum(dl);
+      st.lse2 = fmaxf(t.lse[(int64_t)head * t.q_rows + st.qi + qoff] * kLog2e, -3.402823466e38f);
+      if (qv && lh == 0) {
+        t.delta_w[(int64_t)head * t.q_rows + st.qi + qoff] = st.delta;
+        t.lse2_w[(int64_t)head * t.q_rows + st.qi + qoff] = st.lse2;
+      }
+    } else {
+      st.lse2 = t.lse2[(int64_t)head * t.q_rows + st.qi + qoff];
+      st.delta = t.delta[(int64_t)head * t.q_rows + st.qi + qoff];
+    }
 #pragma unroll
     for (int dt = 0; dt < 4; dt++)
 #pragma unroll
