@@ -166,18 +166,27 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   __syncthreads();
   auto step = [&](const char* cur, char* nxt) {
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = RANGES ? it.kind : (it.kind & 1);
-    have = it.next<RANGES>(q_hi, rb);
+    int cls0 = kFull, cls1 = kFull;
+    bool fast = false;
+    if constexpr (!RANGES) fast = w_rows > 0 && ks + 2 * kTN <= (kind ? min(c1, wq_lo + 1) : c1);
+    if (fast) {
+      // the common step, found with a handful of scalar instructions: this tile and the next one of the same table
+      // row are whole and visible to every row of the wave; the iterator moves by one tile and nothing is classified
+      it.jt++;
+      it.ks += kTN;
+    } else {
+      have = it.next<RANGES>(q_hi, rb);
+      cls0 = w_rows > 0 ? classify32(kind, ks, c1, wq_lo, wq_hi, wrb) : kSkip;
+      cls1 = w_rows > 0 ? classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb) : kSkip;
+    }
+    if (cls0 != kSkip) dq_subtile(st, cur, cur + kTileBytes, 0, ks, kind, c0, c1, c_log2, lane, cls0 == kPartial);
+    // the copies of the next tiles are issued between the two sub-tiles: at the top of the step, right after the
+    // barrier, the copy instructions of the four waves queue behind one another at the address unit (2 % slower)
     if (have) {
       st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
       st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
     }
-    if (w_rows > 0) {
-#pragma unroll
-      for (int kt = 0; kt < 2; kt++) {
-        const int cls = classify32(kind, ks + 32 * kt, c1, wq_lo, wq_hi, wrb);
-        if (cls != kSkip) dq_subtile(st, cur, cur + kTileBytes, kt, ks + 32 * kt, kind, c0, c1, c_log2, lane, cls == kPartial);
-      }
-    }
+    if (cls1 != kSkip) dq_subtile(st, cur, cur + kTileBytes, 1, ks + 32, kind, c0, c1, c_log2, lane, cls1 == kPartial);
     DCP_WAIT_VMCNT(0);
     __syncthreads();
   };

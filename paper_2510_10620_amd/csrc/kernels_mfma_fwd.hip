@@ -67,8 +67,11 @@ __device__ __forceinline__ void fwd_scores32(const FwdState<NQ>& st, const char*
 
 // Scores of a whole 64-key tile every pair of which is visible to the wave: the two 32-key score tiles are two
 // independent MFMA chains, K fragments requested four k-steps ahead of the MFMAs that use them.
-template <int NQ>
-__device__ __forceinline__ void fwd_scores64(const FwdState<NQ>& st, const char* k_lds, f32x16 (&s)[2][NQ]) {
+// DMA: the eight copy instructions of the next K and V tiles are issued here, one per k-step between the MFMAs
+// (kb / vb: the tiles' first rows, lk / lv: the wave's part of the LDS stage they go to).
+template <int NQ, bool DMA>
+__device__ __forceinline__ void fwd_scores64(const FwdState<NQ>& st, const char* k_lds, f32x16 (&s)[2][NQ],
+                                             const void* kb = nullptr, const void* vb = nullptr, unsigned lk = 0, unsigned lv = 0) {
 #pragma unroll
   for (int kt = 0; kt < 2; kt++)
 #pragma unroll
@@ -84,6 +87,12 @@ __device__ __forceinline__ void fwd_scores64(const FwdState<NQ>& st, const char*
 #pragma unroll
   for (int ksd = 0; ksd < 8; ksd++) {
     __builtin_amdgcn_sched_barrier(0);
+    if (DMA) {
+      static_assert(!DMA || kFwdWaves == 4, "four copy instructions per wave and tile");
+      if (ksd < 4) dma16(st.dmak.off[ksd], kb, lk + ksd * 1024);
+      else dma16(st.dmav.off[ksd - 4], vb, lv + (ksd - 4) * 1024);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (ksd + PF < 8) {
 #pragma unroll
       for (int kt = 0; kt < 2; kt++) ka[ksd + PF][kt] = frag_rm(k_lds, st.fa, 32 * kt, ksd + PF);
@@ -255,7 +264,7 @@ __device__ __forceinline__ void fwd_subtile(FwdState<NQ>& st, const char* k_lds,
 template <int NQ>
 __device__ __forceinline__ void fwd_tile64(FwdState<NQ>& st, const char* k_lds, const char* v_lds, float c_log2) {
   f32x16 s[2][NQ];
-  fwd_scores64<NQ>(st, k_lds, s);
+  fwd_scores64<NQ, false>(st, k_lds, s);
   fwd_softmax_pv<NQ>(st, s, v_lds, c_log2);
 }
 
@@ -354,28 +363,51 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
   // one pipeline step: prefetch the next tile into `nxt`, compute the current one from `cur`
   auto step = [&](const char* cur, char* nxt) {
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = RANGES ? it.kind : (it.kind & 1);
-    have = it.next<RANGES>(q_hi, rb);
-    if (have) {
-      st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
-      st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
-    }
-    if (w_rows > 0) {
-      const int cls0 = classify32(kind, ks, c1, wq_lo, wq_hi, wrb), cls1 = classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb);
-      if constexpr (RANGES) {
+    if constexpr (RANGES) {
+      have = it.next<RANGES>(q_hi, rb);
+      if (have) {
+        st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
+        st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
+      }
+      if (w_rows > 0) {
         // tables with per-token ranges: three self-contained paths (measured 4-5 % faster there than the joined form)
+        const int cls0 = classify32(kind, ks, c1, wq_lo, wq_hi, wrb), cls1 = classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb);
         if (cls0 == kFull && cls1 == kFull) {
           fwd_tile64<NQ>(st, cur, cur + kTileBytes, c_log2);
         } else {
           if (cls0 != kSkip) fwd_subtile<NQ>(st, cur, cur + kTileBytes, 0, ks, kind, c0, c1, c_log2, lane, cls0 == kPartial);
           if (cls1 != kSkip) fwd_subtile<NQ>(st, cur, cur + kTileBytes, 1, ks + 32, kind, c0, c1, c_log2, lane, cls1 == kPartial);
         }
-      } else if (cls0 != kSkip || cls1 != kSkip) {
-        // NONE / CAUSAL tables: the score paths join in one softmax + PV section (4 % faster there: no copies of the
-        // accumulators at the merge)
-        f32x16 s[2][NQ];
+      }
+    } else {
+      // NONE / CAUSAL tables: the score paths join in one softmax + PV section (4 % faster there: no copies of the
+      // accumulators at the merge)
+      f32x16 s[2][NQ];
+      bool pv;
+      if (w_rows > 0 && ks + 2 * kTN <= (kind ? min(c1, wq_lo + 1) : c1)) {
+        // The common step, found with a handful of scalar instructions: this tile and the next one of the same table
+        // row are whole and visible to every row of the wave.  The iterator moves by one tile, nothing is classified,
+        // and the copies of the next tile are issued between the score MFMAs: issued back to back at the top of the
+        // step, the copy instructions of the four waves queue behind one another at the address unit and the waves
+        // issue nothing else meanwhile; the general path's scalar bookkeeping costs some hundred issue slots more.
+        it.jt++;
+        it.ks += kTN;
+        fwd_scores64<NQ, true>(st, cur, s, uni_ptr((const char*)kbase + (int64_t)(it.ks + it.moff) * st.dmak.sb),
+                               uni_ptr((const char*)vbase + (int64_t)(it.ks + it.moff) * st.dmav.sb),
+                               lds_addr(nxt) + wave * 4096, lds_addr(nxt + kTileBytes) + wave * 4096);
+        pv = true;
+      } else {
+        have = it.next<RANGES>(q_hi, rb);
+        if (have) {
+          st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
+          st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
+        }
+        const int cls0 = w_rows > 0 ? classify32(kind, ks, c1, wq_lo, wq_hi, wrb) : kSkip;
+        const int cls1 = w_rows > 0 ? classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb) : kSkip;
+        pv = cls0 != kSkip || cls1 != kSkip;
         if (cls0 == kFull && cls1 == kFull) {
-          fwd_scores64<NQ>(st, cur, s);
-        } else {
+          fwd_scores64<NQ, false>(st, cur, s);
+        } else if (pv) {
 #pragma unroll
           for (int kt = 0; kt < 2; kt++) {
             const int cls = kt ? cls1 : cls0;
@@ -389,8 +421,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
             }
           }
         }
-        fwd_softmax_pv<NQ>(st, s, cur + kTileBytes, c_log2);
       }
+      if (pv) fwd_softmax_pv<NQ>(st, s, cur + kTileBytes, c_log2);
     }
     DCP_WAIT_VMCNT(0);
     __syncthreads();  // the copy into `nxt` has landed and `cur` may be overwritten
