@@ -89,8 +89,8 @@ __device__ __forceinline__ void fwd_scores64(const FwdState<NQ>& st, const char*
     __builtin_amdgcn_sched_barrier(0);
     if (DMA) {
       static_assert(!DMA || kFwdWaves == 4, "four copy instructions per wave and tile");
-      if (ksd < 4) dma16(st.dmak.off[ksd], kb, lk + ksd * 1024);
-      else dma16(st.dmav.off[ksd - 4], vb, lv + (ksd - 4) * 1024);
+      if (ksd < 4) st.dmak.issue(ksd, kb, lk);
+      else st.dmav.issue(ksd - 4, vb, lv);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (ksd + PF < 8) {
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
         it.ks += kTN;
         fwd_scores64<NQ, true>(st, cur, s, uni_ptr((const char*)kbase + (int64_t)(it.ks + it.moff) * st.dmak.sb),
                                uni_ptr((const char*)vbase + (int64_t)(it.ks + it.moff) * st.dmav.sb),
-                               lds_addr(nxt) + wave * 4096, lds_addr(nxt + kTileBytes) + wave * 4096);
+                               st.dmak.lds_of(nxt, wave), st.dmav.lds_of(nxt + kTileBytes, wave));
         pv = true;
       } else {
         have = it.next<RANGES>(q_hi, rb);

@@ -118,7 +118,7 @@ __device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int c) {
 // PW = 16 / (waves per workgroup) of the 16 instructions of a tile.
 //
 // The copy is issued from inline assembly in the (scalar base + 32-bit lane offset) form: the
-// lane offsets are computed once per kernel, the base moves on the scalar unit, so a tile costs
+// lane offset is computed once per kernel, the base moves on the scalar unit, so a tile costs
 // no vector-ALU work.  The compiler does not see these copies: the caller must execute
 // DCP_WAIT_VMCNT(0) before the barrier that publishes the tile.  A tile that runs past row_last
 // (ragged end) clamps its rows so that every load reads real data.
@@ -139,55 +139,64 @@ __device__ __forceinline__ const void* uni_ptr(const void* p) {
 
 __device__ __forceinline__ unsigned lds_addr(const void* p) { return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)p; }
 
+// Instruction u of wave w fills tile rows 4 (w + NW u) .. + 3 (NW waves): lane >> 4 picks the row, lane & 15 the
+// physical 16-byte chunk, which receives the logical chunk (lane & 15) ^ swz(row).  The rows of a wave's instructions
+// are 4 NW >= 16 apart, so they share row & 15 and with it the swizzle: one lane offset serves all of them, and
+// instruction u only moves the scalar base by 4 NW u rows.
 template <int PW>
 struct TileDmaT {
-  unsigned off[PW];   // row * stride + chunk of the 16 bytes this lane fetches in instruction u
+  static_assert(PW <= 4, "needs 4 or more waves: the rows of a wave's instructions must be a multiple of 16 apart");
+  static constexpr int NW = 16 / PW;
+  unsigned off0;      // row * stride + chunk of the 16 bytes this lane fetches in instruction 0
   int sb;             // row stride, bytes
-  // instruction u of wave `wave` fills tile rows 4 (wave PW + u) .. + 3: lane >> 4 picks the row, lane & 15 the
-  // physical 16-byte chunk, which receives the logical chunk (lane & 15) ^ swz(row)
-  static __device__ __forceinline__ int row_of(int wave, int lane, int u) { return 4 * (wave * PW + u) + (lane >> 4); }
+  static __device__ __forceinline__ int row0_of(int wave, int lane) { return 4 * wave + (lane >> 4); }
   static __device__ __forceinline__ int chunk_of(int lane, int row) { return ((lane & 15) ^ swz(row)) * 16; }
+  static __device__ __forceinline__ unsigned lds_of(const void* tile, int wave) { return lds_addr(tile) + wave * 1024; }
   __device__ __forceinline__ void init(int wave, int lane, int64_t stride_t) {
     sb = (int)stride_t * 2;
-#pragma unroll
-    for (int u = 0; u < PW; u++) {
-      const int row = row_of(wave, lane, u);
-      off[u] = (unsigned)(row * sb + chunk_of(lane, row));
-    }
+    const int row = row0_of(wave, lane);
+    off0 = (unsigned)(row * sb + chunk_of(lane, row));
+  }
+  // instruction u of a whole tile whose first row is at b (wave-uniform), into the wave's part l0 of the LDS tile
+  __device__ __forceinline__ void issue(int u, const void* b, unsigned l0) const {
+    dma16(off0, (const char*)b + (int64_t)(4 * NW * u) * sb, l0 + u * NW * 1024);
   }
   __device__ __forceinline__ void load(char* tile, const bf16_t* base, int row_start, int row_last, int wave) const {
     // wave-uniform by construction; readfirstlane makes it provably so (it must live in SGPRs)
     const void* b = uni_ptr((const char*)base + (int64_t)row_start * sb);
-    const unsigned l0 = lds_addr(tile) + wave * PW * 1024;
+    const unsigned l0 = lds_of(tile, wave);
     if (row_start + kTN - 1 <= row_last) {
 #pragma unroll
-      for (int u = 0; u < PW; u++) dma16(off[u], b, l0 + u * 1024);
+      for (int u = 0; u < PW; u++) issue(u, b, l0);
     } else {
       // ragged end: rows past row_last repeat it (recomputed here: this path is rare and the lane's
       // row / chunk numbers are not worth registers)
       const int lim = row_last - row_start, lane = threadIdx.x & 63;
+      const int row = row0_of(wave, lane), ch = chunk_of(lane, row);
 #pragma unroll
-      for (int u = 0; u < PW; u++) {
-        const int row = row_of(wave, lane, u);
-        dma16((unsigned)(min(row, lim) * sb + chunk_of(lane, row)), b, l0 + u * 1024);
-      }
+      for (int u = 0; u < PW; u++) dma16((unsigned)(min(row + 4 * NW * u, lim) * sb + ch), b, l0 + u * NW * 1024);
     }
   }
 };
 
 // The same copy with nothing kept in registers between calls (for kernels that have none to spare): the lane
-// offsets are recomputed from an opaque copy of the lane number at every call.
+// offset is recomputed from an opaque copy of the lane number at every call.
 template <int PW>
 __device__ __forceinline__ void tile_dma_lean(char* tile, const bf16_t* base, int sb, int row_start, int row_last, int wave) {
   int lane = threadIdx.x & 63;
   asm volatile("" : "+v"(lane));
   const void* b = uni_ptr((const char*)base + (int64_t)row_start * sb);
-  const unsigned l0 = lds_addr(tile) + wave * PW * 1024;
-  const int lim = row_last - row_start;
+  const unsigned l0 = TileDmaT<PW>::lds_of(tile, wave);
+  constexpr int NW = 16 / PW;
+  const int row = TileDmaT<PW>::row0_of(wave, lane), ch = TileDmaT<PW>::chunk_of(lane, row);
+  if (row_start + kTN - 1 <= row_last) {
+    const unsigned off0 = (unsigned)(row * sb + ch);
 #pragma unroll
-  for (int u = 0; u < PW; u++) {
-    const int row = TileDmaT<PW>::row_of(wave, lane, u);
-    dma16((unsigned)(min(row, lim) * sb + TileDmaT<PW>::chunk_of(lane, row)), b, l0 + u * 1024);
+    for (int u = 0; u < PW; u++) dma16(off0, (const char*)b + (int64_t)(4 * NW * u) * sb, l0 + u * NW * 1024);
+  } else {
+    const int lim = row_last - row_start;
+#pragma unroll
+    for (int u = 0; u < PW; u++) dma16((unsigned)(min(row + 4 * NW * u, lim) * sb + ch), b, l0 + u * NW * 1024);
   }
 }
 
