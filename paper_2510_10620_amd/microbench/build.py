@@ -8,6 +8,8 @@
   lds_bandwidth      ds_read_b128 / ds_read_b64 / ds_read_b64_tr_b16 bytes per clock per CU
   lds_patterns       ds_read_b128 rate of the kernels' swizzled tile layout against other layouts
   mfma_valu_overlap  whether vector-ALU instructions run in the shadow of MFMAs, in one wave and across two waves of a SIMD
+  valu_rates         cycles per wave instruction of v_fma / v_exp / v_max3 / v_cvt_pk_bf16, one and two waves per SIMD
+  lds_copy_issue     cycles a wave spends issuing 4 or 8 global_load_lds_dwordx4, alone and with the workgroup's other waves
   hbm_stream         GB/s of plain read-only, write-only and copy kernels (what the HBM-bound kernels can be held against)
   loop_ingredients   MFMA rate of the attention inner-loop skeleton as LDS operands, softmax ALU work
                      and the barrier are added one by one
