@@ -9,10 +9,10 @@ struct KTensors {
   const void *q, *k, *v, *dout, *out_in;
   void *out, *dq, *dk, *dv;
   float* lse;              // forward: output; backward: input
-  float* delta_w;          // backward, MFMA family: where the dQ kernel leaves delta and lse2 (the same arrays as below) for
-  float* lse2_w;           //   the dK/dV kernel; null when a separate preprocess kernel has filled them
-  const float* delta;      // backward input [Hq,T]
-  const float* lse2;       // backward input [Hq,T]: max(lse * log2(e), -FLT_MAX), made by the preprocess
+  float* delta_w;          // backward, MFMA family: where the dQ kernel leaves -delta and lse2 (the same arrays as below) for
+  float* lse2_w;           //   the dK/dV kernel; null in the scalar family, where a preprocess kernel has filled them
+  const float* delta;      // backward input [Hq,T]: delta (scalar family), -delta (MFMA family dK/dV, from the dQ kernel)
+  const float* lse2;       // backward input [Hq,T]: max(lse * log2(e), -FLT_MAX)
   const int32_t* ranges;   // [T,4] or null (tables without RANGES rows)
   int32_t window, sink;    // window > 0: the table has WINDOW rows; their per-token ranges are worked out, not read
   int32_t masked;          // the table has RANGES or WINDOW rows (rows with per-token ranges)

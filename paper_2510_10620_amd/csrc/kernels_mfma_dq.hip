@@ -119,10 +119,11 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
       st.qf[ks] = as_frag(*(const uint4*)(qp + 16 * ks));
       st.dof[ks] = as_frag(*(const uint4*)(dop + 16 * ks));
     }
-    if (t.delta_w) {
+    {
       // the backward preprocess, fused: delta = sum_d dO * O of the lane's row from the final O, and the saved LSE in
-      // the exp2 domain (clamped to a finite value: a row that saw nothing has every score masked); both are left
-      // in the workspace for the dK/dV kernel, which runs after this one
+      // the exp2 domain (clamped to a finite value: a row that saw nothing has every score masked); -delta and the
+      // LSE are left in the workspace for the dK/dV kernel, which runs after this one and starts its dP accumulators
+      // from -delta
       const bf16_t* outp = (const bf16_t*)t.out_in + (int64_t)(st.qi + qoff) * t.o_st + (int64_t)head * t.o_sh + 8 * lh;
       float dl = 0.f;
 #pragma unroll
@@ -140,12 +141,9 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
       st.delta = xhalf_sum(dl);
       st.lse2 = fmaxf(t.lse[(int64_t)head * t.q_rows + st.qi + qoff] * kLog2e, -3.402823466e38f);
       if (qv && lh == 0) {
-        t.delta_w[(int64_t)head * t.q_rows + st.qi + qoff] = st.delta;
+        t.delta_w[(int64_t)head * t.q_rows + st.qi + qoff] = -st.delta;
         t.lse2_w[(int64_t)head * t.q_rows + st.qi + qoff] = st.lse2;
       }
-    } else {
-      st.lse2 = t.lse2[(int64_t)head * t.q_rows + st.qi + qoff];
-      st.delta = t.delta[(int64_t)head * t.q_rows + st.qi + qoff];
     }
 #pragma unroll
     for (int dt = 0; dt < 4; dt++)

@@ -134,9 +134,18 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
   const char* do_lds = stage + kTileBytes;
   FragAddr2 fa;
   fa.init(lane);
+  // dP starts from -delta of its query rows (element 4a + b of the tile is query row 8a + 4 lh + b), so that the
+  // accumulator ends as dP - delta and dS is one multiplication
+  const float* lse_lds = (const float*)(stage + kStageLse) + 32 * qt + 4 * lh;
+  const float* dl_lds = (const float*)(stage + kStageDelta) + 32 * qt + 4 * lh;
   f32x16 s, dp;
 #pragma unroll
-  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+  for (int a = 0; a < 4; a++) {
+    const float4 d4 = *(const float4*)(dl_lds + 8 * a);
+    dp[4 * a] = d4.x; dp[4 * a + 1] = d4.y; dp[4 * a + 2] = d4.z; dp[4 * a + 3] = d4.w;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; r++) s[r] = 0.f;
   if constexpr (!RANGES) {
     // operands one k-step ahead of the MFMAs that use them (8 more registers in flight; the kernel for tables with
     // per-token ranges has no registers left for it here, where s and dp are live: it spills and gets slower); the
@@ -184,18 +193,16 @@ __device__ __forceinline__ void dkv_subtile(DkvState& st, const char* stage, int
       s[r] = __builtin_amdgcn_inverse_ballot_w64(cond) ? s[r] : -INFINITY;
     }
   }
-  const float* lse_lds = (const float*)(stage + kStageLse) + 32 * qt + 4 * lh;
-  const float* dl_lds = (const float*)(stage + kStageDelta) + 32 * qt + 4 * lh;
 #pragma unroll
   for (int a = 0; a < 4; a++) {
-    const float4 l4 = *(const float4*)(lse_lds + 8 * a), d4 = *(const float4*)(dl_lds + 8 * a);
-    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+    const float4 l4 = *(const float4*)(lse_lds + 8 * a);
+    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
     for (int b = 0; b < 4; b++) {
       const int r = 4 * a + b;
       const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c_log2, -lv[b]));
       s[r] = p;
-      dp[r] = p * (dp[r] - dv4[b]);
+      dp[r] *= p;
     }
   }
   {
