@@ -11,6 +11,7 @@ static constexpr float kLog2e = 1.44269504088896340736f;
 struct DqState {
   bf16x8 qf[8], dof[8];
   f32x16 dq[4];
+  f32x16 neg_delta;   // -delta of the lane's query in every element
   float lse2, delta;  // lse * log2(e) clamped to a finite value (a row that saw nothing has every score masked), delta
   int qi;
   int4 qr;
@@ -21,9 +22,11 @@ struct DqState {
 __device__ __forceinline__ void dq_subtile(DqState& st, const char* k_lds, const char* v_lds, int kt, int ks32,
                                            int kind, int c0, int c1, float c_log2, int lane, bool MASK) {
   const int lh = lane >> 5;
-  f32x16 s, dp;
+  // dP starts from -delta of the lane's query (a block of 16 registers kept for the whole kernel: the first MFMA
+  // reads its accumulator input from there and writes elsewhere), so dS is one multiplication per element
+  f32x16 s, dp = st.neg_delta;
 #pragma unroll
-  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+  for (int r = 0; r < 16; r++) s[r] = 0.f;
 #pragma unroll
   for (int ksd = 0; ksd < 8; ksd++) {
     s = mfma(frag_rm(k_lds, st.fa, 32 * kt, ksd), st.qf[ksd], s);
@@ -41,7 +44,7 @@ __device__ __forceinline__ void dq_subtile(DqState& st, const char* k_lds, const
 #pragma unroll
   for (int r = 0; r < 16; r++) {
     const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c_log2, -st.lse2));
-    s[r] = p * (dp[r] - st.delta);
+    s[r] = p * dp[r];
   }
 #pragma unroll
   for (int c = 0; c < 2; c++) {
@@ -139,6 +142,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
         }
       }
       st.delta = xhalf_sum(dl);
+#pragma unroll
+      for (int r = 0; r < 16; r++) st.neg_delta[r] = -st.delta;
       st.lse2 = fmaxf(t.lse[(int64_t)head * t.q_rows + st.qi + qoff] * kLog2e, -3.402823466e38f);
       if (qv && lh == 0) {
         t.delta_w[(int64_t)head * t.q_rows + st.qi + qoff] = -st.delta;
