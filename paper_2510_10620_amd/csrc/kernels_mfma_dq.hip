@@ -170,8 +170,10 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
   auto step = [&](const char* cur, char* nxt) {
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = RANGES ? it.kind : (it.kind & 1);
     int cls0 = kFull, cls1 = kFull;
-    bool fast = false;
-    if constexpr (!RANGES) fast = w_rows > 0 && ks + 2 * kTN <= (kind ? min(c1, wq_lo + 1) : c1);
+    bool fast;
+    // (rows with per-token ranges take the general path: the test on the range bounds that would spare it costs as
+    // much as it saves here)
+    fast = (!RANGES || kind < 2) && w_rows > 0 && ks + 2 * kTN <= (kind ? min(c1, wq_lo + 1) : c1);
     if (fast) {
       // the common step, found with a handful of scalar instructions: this tile and the next one of the same table
       // row are whole and visible to every row of the wave; the iterator moves by one tile and nothing is classified

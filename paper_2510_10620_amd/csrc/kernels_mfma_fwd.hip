@@ -364,14 +364,23 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
   auto step = [&](const char* cur, char* nxt) {
     const int ks = it.ks, c0 = it.c0, c1 = it.c1, kind = RANGES ? it.kind : (it.kind & 1);
     if constexpr (RANGES) {
-      have = it.next<RANGES>(q_hi, rb);
+      // the same short test as below spares the iterator and the classification: NONE and CAUSAL rows as there, rows
+      // with per-token ranges when one of the two ranges of every row of the wave covers this tile and the next
+      int cls0 = kFull, cls1 = kFull;
+      if (w_rows > 0 && (kind < 2 ? ks + 2 * kTN <= (kind ? min(c1, wq_lo + 1) : c1)
+                                  : ks + 2 * kTN <= c1 && wrb.all_see(ks, ks + 2 * kTN))) {
+        it.jt++;
+        it.ks += kTN;
+      } else {
+        have = it.next<RANGES>(q_hi, rb);
+        if (w_rows > 0) { cls0 = classify32(kind, ks, c1, wq_lo, wq_hi, wrb); cls1 = classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb); }
+      }
       if (have) {
         st.dmak.load(nxt, kbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
         st.dmav.load(nxt + kTileBytes, vbase, it.ks + it.moff, it.c1 - 1 + it.moff, wave);
       }
       if (w_rows > 0) {
         // tables with per-token ranges: three self-contained paths (measured 4-5 % faster there than the joined form)
-        const int cls0 = classify32(kind, ks, c1, wq_lo, wq_hi, wrb), cls1 = classify32(kind, ks + 32, c1, wq_lo, wq_hi, wrb);
         if (cls0 == kFull && cls1 == kFull) {
           fwd_tile64<NQ>(st, cur, cur + kTileBytes, c_log2);
         } else {
