@@ -17,7 +17,8 @@ static constexpr float kLazy = 8.f;  // rescale threshold, log2 units
 #ifndef DCP_FWD_NW
 #define DCP_FWD_NW 4
 #endif
-static constexpr int kFwdWaves = DCP_FWD_NW;   // waves per workgroup (4 or 8)
+static constexpr int kFwdWaves = DCP_FWD_NW;   // waves per workgroup
+static_assert(kFwdWaves == 4, "the step's inline tile copies are written for four waves (four copy instructions per wave and tile)");
 
 template <int NQ>
 struct FwdCfg {
@@ -88,7 +89,6 @@ __device__ __forceinline__ void fwd_scores64(const FwdState<NQ>& st, const char*
   for (int ksd = 0; ksd < 8; ksd++) {
     __builtin_amdgcn_sched_barrier(0);
     if (DMA) {
-      static_assert(!DMA || kFwdWaves == 4, "four copy instructions per wave and tile");
       if (ksd < 4) st.dmak.issue(ksd, kb, lk);
       else st.dmav.issue(ksd - 4, vb, lv);
       __builtin_amdgcn_sched_barrier(0);
