@@ -245,6 +245,19 @@ def test_edge_cases(impl):
     assert ei.value.status in (P.DCP_ERR_UNSUPPORTED, P.DCP_ERR_INVALID_ARG)
 
 
+@pytest.mark.parametrize("kind,B", [("causal", 64), ("causal", 192), ("causal", 1024), ("shared_question", 256), ("lambda", 320)])
+def test_lengths_around_the_tile_grid(kind, B):
+    """Sequence lengths one below, at and one above multiples of the 64-key tile and the 128-row query tile: the steps
+    where a wave passes from the short step (this tile and the next whole and fully visible, copies of the next tile
+    issued between its MFMAs) to the general one, at every offset of the block size against the tiles; causal tables
+    run the kernels without per-token ranges, the other two the kernels with them (NONE, CAUSAL and RANGES rows)."""
+    spec = {"causal": W.MaskSpec("causal"), "shared_question": W.MaskSpec("shared_question"),
+            "lambda": W.MaskSpec("lambda", window=150, sink=70)}[kind]
+    lens = [63, 64, 65, 127, 128, 129, 191, 193, 256, 257, 321, 640, 705]
+    w = W.custom_workload("grid", lens, B, 4, 2, 128, "bf16", spec, seed=77, input_scale=0.5)
+    run_case(w, H.oracle_table(w), IMPLS["auto"], label=f"{kind} B{B}")
+
+
 @pytest.mark.parametrize("B", [32, 96, 4096])
 def test_block_sizes_off_the_tile_grid(B):
     """Block sizes below the kernels' 128-row / 64-key tiles, not a multiple of them, and larger than every
