@@ -10,7 +10,9 @@
  *   - "host" pointers are read during the call and may be freed on return.  "device" pointers
  *     are HIP device memory owned by the caller; the library never frees or keeps them.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Launching calls only
- *     enqueue work on it and return without synchronising.
+ *     enqueue work on it and return without synchronising, with one exception: the first launch
+ *     that uses a plan (or a copy list) on a device uploads its integer arrays, which allocates
+ *     device memory and waits for the stream once; dcp_plan_prepare does that ahead of time.
  *   - Tensors: q, out, dout, dq are [T, Hq, D]; k, v, dk, dv are [T, Hkv, D]; D is contiguous;
  *     token and head strides are given in elements.  lse and delta are float [Hq, T] contiguous.
  *     Query head h reads KV head h / (Hq / Hkv).  T = cu_seqlens[n_seq] packed tokens.
@@ -18,9 +20,9 @@
  * Block numbering (Sec. 4.1 "Block Generation" of the paper): sequence s with L_s tokens is
  * cut into ceil(L_s / block_size) data blocks, the last possibly short; blocks never straddle
  * sequences; global block id = (blocks of earlier sequences) + index inside the sequence.
- * A block-table row (q_blk, kv_blk, mask_kind) is one computation block: "attention between
- * query block Q_i and key-value block KV_j, contributing to output block O_i" (Sec. 4.1).  It
- * applies to every head.  The table DEFINES the mask: a (query, key) pair is visible iff a listed
+ * A block-table row (q_blk, kv_blk, mask_kind) is one computation block of Sec. 4.1: the attention
+ * of query block q_blk against key-value block kv_blk, whose result belongs to output block q_blk.
+ * It applies to every head.  The table DEFINES the mask: a (query, key) pair is visible iff a listed
  * row covers it and the row's predicate holds; pairs not listed are not visible.
  */
 #ifndef DCP_H_
@@ -49,9 +51,9 @@ typedef enum {
  *   NONE   every pair of the tile is visible;
  *   CAUSAL visible iff position(j) <= position(i);
  *   RANGES visible iff packed index of j lies in [r[i][0], r[i][1]) or [r[i][2], r[i][3]) -- the
- *          paper's "arrays specifying the index ranges each token should attend to, at most two
- *          ranges per token" (Sec. 5, Blockwise Attention); r is int32 [T, 4], packed-token
- *          coordinates, half open, an empty range has hi <= lo;
+ *          per-token range arrays of Sec. 5 "Blockwise Attention" (no more than two ranges for a
+ *          token); r is int32 [T, 4], packed-token coordinates, half open, an empty range has
+ *          hi <= lo;
  *   SKIP   never (the row is ignored);
  *   WINDOW sliding window with an attention sink (the lambda-shaped mask of Sec. 2.4; sink 0 gives
  *          the plain sliding window): visible iff j <= i and (i - j < window or j is one of the
@@ -72,7 +74,7 @@ typedef struct dcp_plan dcp_plan_t; /* opaque; created and destroyed by the libr
 /* ---------------------------------------------------------------------------------------------
  * Block generation (Sec. 4.1): from per-token range arrays build the block table.  A computation
  * block is emitted for every same-sequence (q_blk, kv_blk) whose mask tile is not all zeros
- * ("those blocks will not be constructed"), classified NONE (all ones), CAUSAL (tile equals the
+ * (fully masked tiles get no computation block), classified NONE (all ones), CAUSAL (tile equals the
  * causal predicate) or RANGES, in ascending (q_blk, kv_blk) order.
  *   cu_seqlens_host  host int32[n_seq+1]
  *   attn_ranges_host host int32[T,4]
@@ -127,13 +129,23 @@ dcp_status_t dcp_plan_set_block_buffers(dcp_plan_t* plan, const int32_t* q_slot_
  *   table_host    host int32[n_entries,3] rows (q_blk, kv_blk, mask_kind)
  *   out_slot_host host int32[n_entries] or NULL.  NULL: one output per q_blk, written to the
  *                 packed `out`/`lse`.  Otherwise row e accumulates into partial slot out_slot[e]
- *                 (0 <= slot < n_slots); all rows of a slot must share one q_blk ("intermediate
- *                 results pending for reduction", Sec. 5), merged later by dcp_merge_partials.
+ *                 (0 <= slot < n_slots); all rows of a slot must share one q_blk (a slot is one of
+ *                 the not-yet-reduced intermediate results that Sec. 5's block buffers hold),
+ *                 merged later by dcp_merge_partials.
  * n_entries == 0 is legal.  Errors: BAD_CU_SEQLENS, BAD_TABLE, INVALID_ARG. */
 dcp_status_t dcp_plan_create(dcp_plan_t** plan, const int32_t* cu_seqlens_host, int32_t n_seq,
                              int32_t block_size, const int32_t* table_host, int64_t n_entries,
                              const int32_t* out_slot_host, int32_t n_slots);
 dcp_status_t dcp_plan_destroy(dcp_plan_t* plan);
+
+/* Creates now what the launching calls would otherwise create at their first use of the plan: the device copy of the
+ * plan's integer arrays and the work lists of the forward, dQ and dK/dV kernels that (dtype, d, impl) selects, for
+ * hq / hkv heads, on the device that is current.  This is the one place that allocates device memory (hipMalloc)
+ * and waits for `stream` (the upload of the arrays); after it, dcp_block_attn_fwd, dcp_block_attn_bwd and
+ * dcp_merge_partials with this plan and shape only enqueue kernels.  Without it the first of those calls does the same
+ * work itself, once.  Call it after dcp_plan_set_block_buffers, if that is used.  Errors as for the launching calls. */
+dcp_status_t dcp_plan_prepare(dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype, int32_t impl,
+                              void* stream);
 
 /* Parameters of the plan's WINDOW rows: window >= 1 keys including the query, sink >= 0 tokens at the
  * start of every sequence (both at most 2^30).  Launches of a plan with WINDOW rows fail with
@@ -234,7 +246,11 @@ dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* 
 
 /* Gradient reduction across blocks (Sec. 5 "Blockwise Reduction" used on gradients, Sec. 7.5):
  * dst[i] = sum_p parts[p][i], accumulated in fp32, stored as dst_dtype.
- *   parts_dev   device array of n_parts device pointers... passed by value below as host array  */
+ *   parts_host_array_of_device_ptrs  host array of n_parts (1..8) device pointers, read during the
+ *               call; each points to n_elems contiguous elements of parts_dtype
+ *   dst         device, n_elems contiguous elements of dst_dtype, 16-byte aligned like the parts
+ * DCP_ERR_INVALID_ARG: n_parts outside 1..8, a NULL or misaligned pointer, n_elems negative or
+ * not a multiple of 8.  n_elems == 0 is legal (nothing is launched). */
 dcp_status_t dcp_sum_partials(const void* const* parts_host_array_of_device_ptrs, int32_t n_parts,
                               int32_t parts_dtype, void* dst, int32_t dst_dtype, int64_t n_elems,
                               void* stream);
@@ -260,8 +276,8 @@ dcp_status_t dcp_copy_list_destroy(dcp_copy_list_t* list);
 dcp_status_t dcp_blockwise_copy(dcp_copy_list_t* list, const void* src, int64_t src_row_stride,
                                 void* dst, int64_t dst_row_stride, int64_t row_bytes, void* stream);
 
-/* Execution plans (Sec. 5: "an execution plan consists of a sequence of such instructions ... sequentially executed
- * by the executor"; Sec. 4.3: the transfer of one division overlaps the computation of another).  The five instruction
+/* Execution plans (Sec. 5: a plan is a list of instructions that the executor carries out one after the other;
+ * Sec. 4.3: the transfer of one division overlaps the computation of another).  The five instruction
  * types of Sec. 5 map to ops: Blockwise Attention (forward, backward), Blockwise Reduction (LSE merge of partial
  * outputs; plain sum of gradient partials), Blockwise Copy, Comm.Launch and Comm.Wait.  With one device a transfer is
  * a Blockwise Copy handed to a second stream: Comm.Launch starts it after everything issued before it and returns at

@@ -62,6 +62,7 @@ _SIGS = {
     "dcp_plan_create": (ctypes.c_int, [ctypes.POINTER(vp), i32p, ctypes.c_int32, ctypes.c_int32, i32p, ctypes.c_int64, i32p, ctypes.c_int32]),
     "dcp_plan_set_block_buffers": (ctypes.c_int, [vp, i32p, ctypes.c_int32, i32p, ctypes.c_int32]),
     "dcp_plan_destroy": (ctypes.c_int, [vp]),
+    "dcp_plan_prepare": (ctypes.c_int, [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]),
     "dcp_plan_export": (ctypes.c_int, [vp, ctypes.c_int, i32p, ctypes.c_int64, i64p]),
     "dcp_plan_export_dkv_items": (ctypes.c_int, [vp, ctypes.c_int32, i32p, ctypes.c_int64, i64p]),
     "dcp_block_attn_fwd": (ctypes.c_int, [vp, ctypes.POINTER(Tensors), vp]),

@@ -145,6 +145,11 @@ def dcp_plan_set_block_buffers(plan, q_slot, n_q_slots, kv_slot, n_kv_slots):
     plan.q_rows, plan.kv_rows = n_q_slots * plan.block_size, n_kv_slots * plan.block_size
 
 
+def dcp_plan_prepare(plan, hq, hkv, d, dtype_code, impl=DCP_IMPL_AUTO):
+    """Uploads the plan's arrays and work lists for this shape now (the only call that allocates and synchronises)."""
+    _check(_lib.load().dcp_plan_prepare(plan.handle, hq, hkv, d, dtype_code, impl, _stream()))
+
+
 def dcp_plan_destroy(plan):
     _check(_lib.load().dcp_plan_destroy(plan.handle))
     plan.handle = None

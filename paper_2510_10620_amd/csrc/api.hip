@@ -107,6 +107,24 @@ static KTensors pack(const dcp_plan_t* plan, const dcp_tensors_t* t) {
   return k;
 }
 
+extern "C" dcp_status_t dcp_plan_prepare(dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype, int32_t impl,
+                                         void* stream) {
+  if (!plan) return fail(DCP_ERR_INVALID_ARG, "plan is NULL");
+  dcp_tensors_t t{};
+  t.hq = hq; t.hkv = hkv; t.d = d; t.dtype = dtype; t.impl = impl; t.softmax_scale = 1.f;
+  dcp_status_t st = check_shape(&t);
+  if (st != DCP_OK) return st;
+  bool use_mfma = false;
+  if ((st = pick_impl(&t, &use_mfma)) != DCP_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  if ((st = plan->ensure_device(s)) != DCP_OK) return st;
+  if (plan->total_tokens == 0) return DCP_OK;
+  DevGroup g;
+  if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g)) != DCP_OK) return st;
+  if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &g)) != DCP_OK) return st;
+  return plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &g, use_mfma ? hkv : 0);
+}
+
 extern "C" dcp_status_t dcp_block_attn_fwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* stream) {
   if (!plan) return fail(DCP_ERR_INVALID_ARG, "plan is NULL");
   dcp_status_t st = check_shape(t);

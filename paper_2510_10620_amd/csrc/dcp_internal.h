@@ -113,10 +113,12 @@ struct dcp_plan {
   std::map<ItemKey, dcp::HostItems> h_items;
   std::map<ItemKey, dcp::DevItems> items;
 
-  dcp_status_t ensure_device(hipStream_t stream);
+  // may_alloc = false: fail (DCP_ERR_INVALID_ARG) instead of creating a device copy that does not exist yet
+  dcp_status_t ensure_device(hipStream_t stream, bool may_alloc = true);
   // group id: 0 fwd, 1 bwdq, 2 bwdkv.  Host only; takes the plan's lock.
   const dcp::HostItems& host_items(int group_id, int tile_rows, int split_heads);
-  dcp_status_t group_for(int group_id, int tile_rows, hipStream_t stream, dcp::DevGroup* out, int split_heads = 0);
+  dcp_status_t group_for(int group_id, int tile_rows, hipStream_t stream, dcp::DevGroup* out, int split_heads = 0,
+                         bool may_alloc = true);
 };
 
 // Blockwise Copy list: validated entries cut into chunks of at most kCopyChunkRows rows.

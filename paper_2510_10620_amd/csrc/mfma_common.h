@@ -122,12 +122,18 @@ __device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int c) {
 // no vector-ALU work.  The compiler does not see these copies: the caller must execute
 // DCP_WAIT_VMCNT(0) before the barrier that publishes the tile.  A tile that runs past row_last
 // (ragged end) clamps its rows so that every load reads real data.
+// M0 is written inside the statement, so it is on the clobber list: the backend then sees the write (its pass that
+// merges M0 initialisations must not carry a value across these statements).  The compiler's note that it will not
+// save and restore a reserved register around the statement is expected here: nothing else in these kernels keeps M0.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(unsigned voffset, const void* sbase, unsigned lds) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voffset), "s"(sbase), "s"(lds) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voffset), "s"(sbase), "s"(lds) : "memory", "m0");
 }
 __device__ __forceinline__ void dma4(unsigned voffset, const void* sbase, unsigned lds) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voffset), "s"(sbase), "s"(lds) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voffset), "s"(sbase), "s"(lds) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 // a pointer that is wave-uniform by construction, made provably so (it must live in SGPRs)
 __device__ __forceinline__ const void* uni_ptr(const void* p) {
   const uint64_t v = (uint64_t)p;

@@ -454,7 +454,7 @@ extern "C" dcp_status_t dcp_plan_export(const dcp_plan_t* plan, dcp_export_t whi
 
 // ------------------------------------------------------------------------------------------------
 // device mirror
-dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
+dcp_status_t dcp_plan::ensure_device(hipStream_t stream, bool may_alloc) {
   std::lock_guard<std::mutex> lock(mu);
   int cur = 0;
   DCP_HIP_TRY(hipGetDevice(&cur));
@@ -462,6 +462,7 @@ dcp_status_t dcp_plan::ensure_device(hipStream_t stream) {
     if (cur != device) return fail(DCP_ERR_INVALID_ARG, "plan was first used on another device");
     return DCP_OK;
   }
+  if (!may_alloc) return fail(DCP_ERR_INVALID_ARG, "the plan has no device copy yet: call dcp_plan_prepare first");
   std::vector<int32_t> host;
   auto put = [&](const std::vector<int32_t>& v) {
     size_t off = host.size();
@@ -677,8 +678,8 @@ static dcp_status_t upload(const std::vector<T>& v, T** dev, hipStream_t stream)
   return DCP_OK;
 }
 
-dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, DevGroup* out, int split_heads) {
-  dcp_status_t st = ensure_device(stream);
+dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, DevGroup* out, int split_heads, bool may_alloc) {
+  dcp_status_t st = ensure_device(stream, may_alloc);
   if (st != DCP_OK) return st;
   const HostItems& hi = host_items(gid, tile_rows, split_heads);
   std::lock_guard<std::mutex> lock(mu);
@@ -686,6 +687,7 @@ dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, Dev
   const ItemKey key(gid, tile_rows, split_heads);
   auto it = items.find(key);
   if (it == items.end()) {
+    if (!may_alloc) return fail(DCP_ERR_INVALID_ARG, "the plan has no work list for this shape yet: call dcp_plan_prepare first");
     DevItems di;
     di.n_items = (int32_t)hi.items.size();
     di.n_reduce = (int32_t)hi.reduce.size();

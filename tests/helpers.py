@@ -139,43 +139,56 @@ def max_abs(a, b):
     return float(np.nan_to_num(d, nan=np.inf, posinf=np.inf).max())
 
 
-def max_scaled(a, b, knee, by_row=False):
-    """max |a - b| / max(1, |b| / knee): the absolute error where |b| <= knee, and the error
-    relative to |b| / knee above it.  by_row: |b| is replaced by the largest |b| of the element's
-    row (last axis)."""
+def err_stats(a, b, knee, by_row=False):
+    """Errors of a against the reference b, split at |b| = knee: `raw` the largest |a - b| anywhere, `low` the largest
+    |a - b| where |b| < knee, `high_rel` the largest |a - b| / |b| where |b| >= knee, `max_ref` the largest |b|.
+    by_row: the magnitude that decides the side and divides the error is the largest |b| of the element's row
+    (last axis) instead of the element's own."""
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
     cmp = _cmp_mask(a, b)
     if not cmp.any():
-        return 0.0
+        return dict(raw=0.0, low=0.0, high_rel=0.0, max_ref=0.0)
     mag = np.abs(b)
     if by_row:
         mag = np.broadcast_to(np.where(np.isfinite(mag), mag, 0.0).max(axis=-1, keepdims=True), b.shape)
-    d = np.abs(a[cmp] - b[cmp]) / np.maximum(1.0, mag[cmp] / knee)
-    return float(np.nan_to_num(d, nan=np.inf, posinf=np.inf).max())
+    d = np.nan_to_num(np.abs(a[cmp] - b[cmp]), nan=np.inf, posinf=np.inf)
+    m = mag[cmp]
+    lo, hi = m < knee, m >= knee
+    return dict(raw=float(d.max()), low=float(d[lo].max()) if lo.any() else 0.0,
+                high_rel=float((d[hi] / m[hi]).max()) if hi.any() else 0.0,
+                max_ref=float(np.where(np.isfinite(np.abs(b[cmp])), np.abs(b[cmp]), 0.0).max()))
 
 
-# Tolerances.  LSE (fp32): max abs 1e-5.  fp32 I/O: max abs 1e-4.  bf16 I/O: max abs 2e-2 for
-# |reference| <= 2.  Above that the bf16 output grid itself approaches and then exceeds 2e-2
-# (half an ulp is 2^-8 |x|: 0.0156 on [4, 8), 0.031 on [8, 16)), and the bf16 rounding of the
-# P / dS MFMA operands adds its own accumulated share, so the bound grows in proportion to the
-# magnitude: 2e-2 * |ref| / 2 = 1e-2 |ref|, about 2.5 bf16 half-ulps.
-# by_row (only where a test says why): a gradient row that sums very many large terms which cancel.
-# All D elements of the row share the coefficients (P or dS) whose rounding to bf16 makes the error, so
-# the error of every element is about 2^-9 of the row's root-mean-square, whatever the element's own
-# value; the row's largest |ref| (2.5-3 rms) then takes the place of |ref| in the bound above.
-TOL = {"bf16": dict(o=2e-2, lse=1e-5, knee=2.0), "f32": dict(o=1e-4, lse=1e-5, knee=None)}
+# Tolerances.  LSE (fp32): max abs 1e-5.  fp32 I/O: max abs 1e-4.  bf16 I/O: plain max abs 2e-2 wherever
+# |reference| < 4.  From 4 on the bf16 output grid alone uses up that bound (half an ulp is 2^-8 of the binade's
+# upper end: 0.0156 on [4, 8), 0.031 on [8, 16)), so there the bound is relative: |error| <= 5e-3 |reference|
+# (= 2e-2 at the knee, about 1.3 bf16 half-ulps everywhere above it).  Only dV reaches such values (the first keys of
+# a sequence, seen by every later query, with dO ~ N(0, 1)).
+# by_row (only where a test says why): a gradient row that sums very many large terms which cancel.  All D elements
+# of the row share the coefficients (P or dS) whose rounding to bf16 makes the error, so the error of every element
+# is about 2^-9 of the row's root-mean-square, whatever the element's own value; the row's largest |ref| then takes
+# the place of |ref| in the bound above.
+TOL = {"bf16": dict(o=2e-2, lse=1e-5, knee=4.0, rel=5e-3), "f32": dict(o=1e-4, lse=1e-5, knee=None, rel=None)}
 
 
-def check(w, got, ref, names, label="", verbose=False, by_row=False):
+def check(w, got, ref, names, label="", verbose=True, by_row=()):
+    """Asserts the tolerances above for every named tensor; returns {name: raw max abs error}.  by_row: names of the
+    tensors judged by row.  The raw error, the error below the knee and the relative error above it are printed
+    (pytest shows them with -rA or -s)."""
     tol = TOL[w.dtype]
-    errs = {}
+    errs, lines = {}, []
     for n in names:
         if n == "lse" or tol["knee"] is None:
             err, lim = max_abs(got[n], ref[n]), (tol["lse"] if n == "lse" else tol["o"])
-        else:
-            err, lim = max_scaled(got[n], ref[n], tol["knee"], by_row), tol["o"]
-        errs[n] = err
-        assert err <= lim, f"{label} {n}: max err {err:.3e} > {lim:.1e}"
-    if verbose:
-        print(label, {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+            errs[n] = err
+            lines.append(f"{n} {err:.2e}")
+            assert err <= lim, f"{label} {n}: max abs err {err:.3e} > {lim:.1e}"
+            continue
+        st = err_stats(got[n], ref[n], tol["knee"], n in by_row)
+        errs[n] = st["raw"]
+        lines.append(f"{n}{' [by row]' if n in by_row else ''} raw {st['raw']:.2e} (|ref|<{tol['knee']:g}: {st['low']:.2e}; above: rel {st['high_rel']:.2e}; max|ref| {st['max_ref']:.2f})")
+        assert st["low"] <= tol["o"], f"{label} {n}: max abs err {st['low']:.3e} > {tol['o']:.1e} where |ref| < {tol['knee']:g}"
+        assert st["high_rel"] <= tol["rel"], f"{label} {n}: relative err {st['high_rel']:.3e} > {tol['rel']:.1e} where |ref| >= {tol['knee']:g}"
+    if verbose or by_row:
+        print(label, "; ".join(lines), flush=True)
     return errs

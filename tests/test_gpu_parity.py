@@ -73,9 +73,10 @@ def test_window_kind_rows_need_no_range_array(window, sink, impl):
     ref = H.oracle_full(w, tensors, table, window=(window, sink))
     # window 1 + sink 1: every query gives the sink key a weight near 1/2, so that key's dK / dV rows are sums of a
     # thousand large terms that cancel (|dV| up to 70 beside elements near 0); the rounding of P and dS to bf16
-    # before the second GEMM costs about 2^-9 * sqrt(2000) * |term| in every element of the row: bound by row
+    # before the second GEMM costs about 2^-9 * sqrt(2000) * |term| in every element of the row: dK and dV of this one
+    # case are bounded by row (the raw errors are printed)
     H.check(w, dict(out=out, lse=lse, dq=dq, dk=dk, dv=dv), ref, ALL, f"window-kind {window}/{sink}/{impl}",
-            by_row=(window == 1))
+            by_row=("dk", "dv") if window == 1 else ())
 
 
 @pytest.mark.parametrize("seed", range(6))
@@ -203,7 +204,7 @@ def test_share_with_divisions_and_merge(impl):
         qb = int(slot_q[s])
         r0, n = int(part["blk_start"][qb]), int(part["blk_end"][qb] - part["blk_start"][qb])
         ps = H.oracle_full(w, tensors, table, select=rows, bwd=False, seqs=[int(part["blk_seq"][qb])])
-        assert H.max_scaled(o_part[s, :n], ps["out"][r0:r0 + n], 2.0) <= 2e-2
+        assert H.max_abs(o_part[s, :n], ps["out"][r0:r0 + n]) <= 2e-2
         assert H.max_abs(lse_part[s, :, :n], ps["lse"][:, r0:r0 + n]) <= 1e-5
     dq, dk, dv = g.backward(out=gfull.out, lse=gfull.lse)
     H.check(w, dict(dq=dq, dk=dk, dv=dv), ref, ("dq", "dk", "dv"), "share bwd")

@@ -574,3 +574,88 @@ def test_comm_volume_invariants_on_random_placements():
     r = OP.comm_volume(blk_len, table, owner, owner[table[:, 0]], 3, 8, 4, 8)
     rows = sum(int(blk_len[k]) * 4 for q, k, _ in table if owner[q] != owner[k])
     assert r["pairwise"] == rows
+
+
+# ---------------------------------------------------------------- masks.causal_blockwise: hand case at the paper's parameters
+def test_causal_blockwise_hand_case_at_the_papers_parameters():
+    """Sec. 7.1 "Attention Masks": mask blocks of 256 tokens, a sliding window of 2 blocks, one sink block, and the
+    final block (the test sample) attends to everything before it.  Six mask blocks, L = 1536; counts worked out by
+    hand from that description: a token of block 0, 1 or 2 sees every earlier token (block 2's window is blocks 1-2
+    and block 0 is the sink), a token i of block 3 sees the sink block (256) and blocks 2-3 up to itself (i - 511), a
+    token of block 4 the sink and blocks 3-4 up to itself (i - 767), a token of the last block everything (i + 1)."""
+    L = 1536
+    M = Mk.causal_blockwise(L, 256, 2, 1)
+    n = M.sum(axis=1)
+    hand = {0: 1, 255: 256, 256: 257, 600: 601, 767: 768, 768: 256 + 257, 1023: 256 + 512, 1024: 256 + 257,
+            1279: 256 + 512, 1280: 1281, 1535: 1536}
+    for i, c in hand.items():
+        assert n[i] == c, (i, n[i], c)
+    # rows 0..767: 768 * 769 / 2 = 295 296; blocks 3 and 4: 256 * 256 + (257 + ... + 512) = 163 968 each;
+    # last block: 1281 + ... + 1536 = 360 576
+    assert int(n.sum()) == 295296 + 2 * 163968 + 360576 == 983808
+    # single pairs: a token of block 3 sees the sink and block 2 but not block 1; the test sample sees block 1
+    assert M[800, 100] and M[800, 520] and not M[800, 300] and not M[800, 801]
+    assert M[1300, 300] and M[1279, 255] and not M[1279, 256] and not M[1279, 767] and M[1279, 768]
+    # a ragged sequence: the last, short block (tokens 1280..1399) is the test sample
+    M2 = Mk.causal_blockwise(1400, 256, 2, 1)
+    assert M2[1399].sum() == 1400 and M2[1280].sum() == 1281 and M2[1279].sum() == 768
+    # rows [r0, r1) of the same mask
+    assert np.array_equal(Mk.causal_blockwise(L, 256, 2, 1, 700, 1300), M[700:1300])
+
+
+def test_sum_partials_hand_values():
+    parts = np.array([[[1.0, 2.0], [3.0, -4.0]], [[10.0, 20.0], [30.0, 40.0]], [[100.0, 200.0], [300.0, 0.5]]])
+    np.testing.assert_array_equal(A.sum_partials(parts), np.array([[111.0, 222.0], [333.0, 36.5]]))
+    np.testing.assert_array_equal(A.sum_partials(parts[:1]), parts[0])
+    # fp64 accumulation of values an fp32 sum would lose
+    np.testing.assert_array_equal(A.sum_partials(np.array([[1e8], [1.0], [-1e8]])), np.array([1.0]))
+
+
+# ---------------------------------------------------------------- the linear-time closed forms of tests/closed_forms.py
+@pytest.mark.parametrize("spec", [W.MaskSpec("causal"), W.MaskSpec("lambda", window=40, sink=9),
+                                  W.MaskSpec("causal_blockwise", window=2, sink=1, mblock=16), W.MaskSpec("shared_question")],
+                         ids=lambda s: s.kind)
+@pytest.mark.parametrize("share", [False, True], ids=["full", "share"])
+def test_closed_forms_agree_with_the_oracle(spec, share):
+    """The table-driven closed forms that the full-size GPU tests compare every element with (uniform softmax for
+    Q = 0 and for identical keys) against the dense oracle on a small ragged batch, for a full table and for one
+    device's share of it (global LSE and O)."""
+    from tests.closed_forms import identical_k_dk, q0_closed_form
+    w = W.custom_workload("cf", [150, 77, 260], 64, 4, 2, 16, "f32", spec, seed=5)
+    cu, B, scale = w.cu_seqlens, w.block_size, w.softmax_scale
+    rng = np.random.default_rng(77)
+    T = w.total_tokens
+    q = rng.standard_normal((T, 4, 16))
+    v = rng.standard_normal((T, 2, 16))
+    do = rng.standard_normal((T, 4, 16))
+    k = np.zeros((T, 2, 16))
+    for s in range(len(cu) - 1):
+        k[cu[s]:cu[s + 1]] = rng.standard_normal((1, 2, 16))           # all keys of a sequence identical
+    table = Bk.table_from_mask(mask_rows_fn(spec), cu, B)
+    sub = table[W.deal_share(len(table), 3, 11, 0)] if share else table
+    vis_full, vis = Bk.Visibility(cu, B, table, w.ranges), Bk.Visibility(cu, B, sub, w.ranges)
+    Og, Lg = A.attention_fwd(q, k, v, cu, vis_full, scale)
+    O, LSE = A.attention_fwd(q, k, v, cu, vis, scale)
+    dq, dk, dv = A.attention_bwd(q, k, v, do, cu, vis, scale, lse=Lg, delta=A.delta_rows(Og, do))
+    n_glob, O_glob, _ = q0_closed_form(w, table, v, do)
+    n, O_cf, dV_cf = q0_closed_form(w, sub, v, do, n_glob)
+    s_i = scale * np.einsum("thd,thd->ht", q, np.repeat(k, 2, axis=1))
+    with np.errstate(divide="ignore"):
+        np.testing.assert_allclose(LSE, np.where(n > 0, s_i + np.log(n), -np.inf), atol=1e-12)
+    np.testing.assert_allclose(O, np.repeat(O_cf, 2, axis=1), atol=1e-5)
+    np.testing.assert_allclose(dv, dV_cf, atol=1e-4)
+    for kvh in range(2):
+        np.testing.assert_allclose(dk[:, kvh], identical_k_dk(w, sub, q, v, do, kvh, n_glob, O_glob), atol=1e-4)
+    # dQ: zero for a full table; for a share scale * k * (n / N) dO . (O_share - O_global)
+    coef = (n / np.maximum(n_glob, 1))[None, :] * np.einsum("thd,thd->ht", do, np.repeat(O_cf - O_glob, 2, axis=1))
+    np.testing.assert_allclose(dq, scale * coef.T[:, :, None] * np.repeat(k, 2, axis=1), atol=1e-5)
+    if not share:
+        assert np.abs(dq).max() < 1e-5
+    # Q = 0 on the same batch: LSE = ln n, same O and dV, dK = 0
+    z = np.zeros_like(q)
+    O0, L0 = A.attention_fwd(z, k, v, cu, vis, scale)
+    _, dk0, dv0 = A.attention_bwd(z, k, v, do, cu, vis, scale, lse=np.where(n_glob > 0, np.log(np.maximum(n_glob, 1)), -np.inf)[None, :].repeat(4, 0),
+                                  delta=A.delta_rows(np.repeat(O_glob, 2, axis=1), do))
+    np.testing.assert_allclose(O0, np.repeat(O_cf, 2, axis=1), atol=1e-5)
+    np.testing.assert_allclose(dv0, dV_cf, atol=1e-4)
+    assert np.abs(dk0).max() < 1e-12
