@@ -14,8 +14,8 @@ namespace dcp {
 struct ProfRec { hipEvent_t a, b; };
 static bool g_prof_on = false;
 static std::vector<ProfRec> g_prof[7];
-ProfScope::ProfScope(int id_, hipStream_t s_) : id(id_), s(s_) {
-  if (!g_prof_on) return;
+ProfScope::ProfScope(int id_, hipStream_t s_, bool enabled) : id(id_), s(s_) {
+  if (!g_prof_on || !enabled) return;
   hipEvent_t a = nullptr;
   if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { stop = nullptr; return; }
   (void)hipEventRecord(a, s);
@@ -222,8 +222,10 @@ extern "C" size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, in
   return bwd_workspace(const_cast<dcp_plan_t*>(plan), hq, hkv, d, dtype).total();
 }
 
-extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace,
-                                           size_t workspace_bytes, void* stream) {
+// The backward behind both of its entry points.  may_alloc = false: the plan's device copies must exist already
+// (dcp_plan_prepare) and no per-kernel timing events are created, so the call neither allocates nor synchronises.
+dcp_status_t dcp::bwd_launch(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace, size_t workspace_bytes, hipStream_t s,
+                             bool may_alloc) {
   if (!plan) return fail(DCP_ERR_INVALID_ARG, "plan is NULL");
   dcp_status_t st = check_shape(t);
   if (st != DCP_OK) return st;
@@ -245,10 +247,9 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
   const size_t need = wsz.total();
   if (!workspace || workspace_bytes < need) return fail(DCP_ERR_WORKSPACE, "workspace is NULL or smaller than dcp_bwd_workspace_bytes");
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(DCP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-  hipStream_t s = (hipStream_t)stream;
   DevGroup gq, gkv;
-  if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &gq)) != DCP_OK) return st;
-  if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv, use_mfma ? t->hkv : 0)) != DCP_OK) return st;
+  if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &gq, 0, may_alloc)) != DCP_OK) return st;
+  if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv, use_mfma ? t->hkv : 0, may_alloc)) != DCP_OK) return st;
   KTensors k = pack(plan, t);
   const size_t n_hT = wsz.n_hT;
   k.part = (float*)((char*)workspace + 2 * wsz.n_hT + wsz.n_bounds);
@@ -266,16 +267,21 @@ extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t
     k.delta_w = delta;
     k.lse2_w = lse2;
   } else {
-    ProfScope ps(DCP_K_DELTA, s);
+    ProfScope ps(DCP_K_DELTA, s, may_alloc);
     if ((st = stream_delta(t->out, t->o_stride_t, t->o_stride_h, t->dout, t->do_stride_t, t->do_stride_h, delta,
                            t->lse, lse2, plan->q_rows, t->hq, t->d, t->dtype, s)) != DCP_OK) return st;
   }
   {
-    ProfScope ps(DCP_K_DQ, s);
+    ProfScope ps(DCP_K_DQ, s, may_alloc);
     if ((st = use_mfma ? mfma_bwd_dq(gq, k, s) : scalar_bwd_dq(gq, k, t->dtype, s)) != DCP_OK) return st;
   }
-  ProfScope ps(DCP_K_DKV, s);
+  ProfScope ps(DCP_K_DKV, s, may_alloc);
   return use_mfma ? mfma_bwd_dkv(gkv, k, s) : scalar_bwd_dkv(gkv, k, t->dtype, s);
+}
+
+extern "C" dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  return bwd_launch(plan, t, workspace, workspace_bytes, (hipStream_t)stream, true);
 }
 
 extern "C" dcp_status_t dcp_sum_partials(const void* const* parts, int32_t n_parts, int32_t parts_dtype, void* dst,

@@ -43,9 +43,13 @@ struct ProfScope {
   int id;
   hipStream_t s;
   hipEvent_t stop = nullptr;
-  ProfScope(int id, hipStream_t s);
+  ProfScope(int id, hipStream_t s, bool enabled = true);
   ~ProfScope();
 };
+
+// the backward behind dcp_block_attn_bwd (api.hip); may_alloc = false: fail rather than create device copies or events
+dcp_status_t bwd_launch(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace, size_t workspace_bytes, hipStream_t s,
+                        bool may_alloc);
 
 // scalar fp32-ALU family (any dtype; D in {32, 64, 128})
 bool scalar_supports(int32_t d);

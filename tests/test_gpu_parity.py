@@ -540,3 +540,78 @@ def test_execution_plan_with_divisions_and_transfers():
     # a program with transfers refuses to run on one stream
     with pytest.raises(P.DcpError):
         prog.run(None)
+
+
+def test_two_runs_are_bit_identical():
+    """No atomics, fixed reduction orders: forward, merge and backward run twice on the same inputs give the same
+    bits, with cut dK/dV items (fp32 partial sums added up by the reduce kernel) and with partial output slots."""
+    import torch
+    import paper_2510_10620_amd as P
+    lens = W.draw_lengths(8192, "lognormal", 512, 4096, seed=2, median=1024)
+    w = W.custom_workload("twice", lens, 256, 8, 2, 128, "bf16", W.MaskSpec("causal"), seed=51, input_scale=1.0 / np.sqrt(128))
+    tensors = W.make_tensors(w)
+    table = H.oracle_table(w)
+    slot, n_slots, _ = W.deal_divisions(table[:, 0], 3, 52)
+    for label, args in (("plain", ()), ("slots", (slot, n_slots))):
+        g = H.GpuRun(w, tensors, table, *args)
+        if label == "plain":
+            assert (P.dcp_plan_export_dkv_items(g.plan, w.hkv)[:, 4] >= 0).any(), "the case is meant to have cut dK/dV items"
+        runs = []
+        for rep in range(2):
+            g.out.fill_(float("nan")); g.lse.fill_(float("nan"))
+            g.forward_only()
+            g.backward_only(g.out, g.lse)
+            runs.append({n: getattr(g, n).clone() for n in ALL})
+        for n in ALL:
+            assert torch.equal(runs[0][n].view(torch.int16 if n != "lse" else torch.int32),
+                               runs[1][n].view(torch.int16 if n != "lse" else torch.int32)), f"{label}: {n} differs between two runs"
+
+
+def test_execution_plan_inline_copy_and_gradient_sum():
+    """The two instruction types the division test does not use: an in-line Blockwise Copy (it runs on the compute
+    stream, in order) that fills the K / V tensors the attention then reads, and Blockwise Reduction used on gradients
+    (the plain sum): the table is dealt to two shares, each share's backward leaves its partial dQ / dK / dV in
+    buffers of its own, and three sums add them up.  Checked against the oracle's full gradients, on two replays."""
+    import torch
+    import paper_2510_10620_amd as P
+    w = W.custom_workload("exec_sum", [420, 130, 77], 64, 4, 2, 128, "bf16", W.MaskSpec("lambda", window=150, sink=12), seed=53,
+                          input_scale=0.5)
+    tensors = W.make_tensors(w)
+    table = H.oracle_table(w)
+    T = w.total_tokens
+    part = OB.block_partition(w.cu_seqlens, w.block_size)
+    bs, bl = part["blk_start"], part["blk_end"] - part["blk_start"]
+    tq, tdo = H.to_torch(w, tensors["q"]), H.to_torch(w, tensors["dout"])
+    k_src, v_src = H.to_torch(w, tensors["k"]), H.to_torch(w, tensors["v"])
+    tk = torch.full_like(k_src, float("nan"))
+    tv = torch.full_like(v_src, float("nan"))
+    rg = torch.from_numpy(np.ascontiguousarray(w.ranges)).cuda()
+    out = torch.full((T, w.hq, w.d), float("nan"), dtype=tq.dtype, device="cuda")
+    lse = torch.full((w.hq, T), float("nan"), dtype=torch.float32, device="cuda")
+    full = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)
+    cl = P.CopyList(np.stack([bs, bs, bl], axis=1).astype(np.int32), T, T)     # every block, block by block
+    instrs = [P.instr_copy(cl, k_src, tk), P.instr_copy(cl, v_src, tv),
+              P.instr_attn_fwd(full, tq, tk, tv, out, lse, w.softmax_scale, rg)]
+    parts = {n: [] for n in ("dq", "dk", "dv")}
+    for share in range(2):
+        rows = W.deal_share(len(table), 2, 54, share)
+        pl = P.dcp_plan_create(w.cu_seqlens, w.block_size, table[rows])
+        ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(pl, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
+        g = [torch.full((T, h, w.d), float("nan"), dtype=tq.dtype, device="cuda") for h in (w.hq, w.hkv, w.hkv)]
+        for n, t in zip(("dq", "dk", "dv"), g):
+            parts[n].append(t)
+        instrs.append(P.instr_attn_bwd(pl, tq, tk, tv, out, lse, tdo, g[0], g[1], g[2], w.softmax_scale, ws, rg))
+    total = {n: torch.full_like(parts[n][0], float("nan")) for n in parts}
+    for n in ("dq", "dk", "dv"):
+        instrs.append(P.instr_sum(parts[n], total[n]))
+    prog = P.Program(instrs)
+    ref = H.oracle_full(w, tensors, table)
+    for rep in range(2):
+        if rep == 1:
+            for t in (tk, tv, out, lse, *total.values()):
+                t.fill_(float("nan"))
+        prog.run()                                   # no transfers: one stream is enough
+        torch.cuda.synchronize()
+        assert torch.equal(tk.view(torch.int16), k_src.view(torch.int16)) and torch.equal(tv.view(torch.int16), v_src.view(torch.int16))
+        got = dict(out=H.from_torch(out), lse=H.from_torch(lse), **{n: H.from_torch(total[n]) for n in total})
+        H.check(w, got, ref, ALL, f"in-line copy + gradient sum, replay {rep}")
