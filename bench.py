@@ -113,6 +113,7 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--only-short", type=int, default=0, help="print only the short-sequence section for this sequence length")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -124,6 +125,9 @@ def main():
     from paper_2510_10620_amd import workloads as W
 
     torch.cuda.set_device(0)
+    if args.only_short:
+        print(json.dumps(short_section(torch, P, W, np, steps=5, seq_len=args.only_short)))
+        return
     w = W.make_workload(args.config)
     table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
     pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, table, w.ranges).sum())
@@ -202,6 +206,7 @@ def main():
     if not args.no_extra:
         extra["share"] = share_section(torch, P, W, np, steps=max(3, args.steps // 4), warmup=2)
         extra["blockwise_copy"] = copy_section(torch, P, np, plan, q, steps=max(3, args.steps // 2))
+        extra["short_sequences"] = short_section(torch, P, W, np, steps=5)
         extra["other_masks"] = masks_section(torch, P, W, np, steps=3)
         extra["execution_plan"] = executor_section(torch, P, W, np, steps=3)
 
@@ -393,6 +398,46 @@ def masks_section(torch, P, W, np, steps):
                            visible_pairs=pairs, ms_per_step=round(ms, 3),
                            tflops=round(14 * pairs * w.hq * w.d / (ms * 1e-3) / 1e12, 1))
         del q, k, v, do, out, lse, dq, dk, dv, ws, plan
+    return res
+
+
+def short_section(torch, P, W, np, steps, seq_len=1024, tokens=65536):
+    """The headline step on a batch of short sequences: the same 65 536 tokens, heads and block size as config 2, cut
+    into equal causal sequences of 1 024 tokens (the short end of the paper's length-scale 0.5 batches, Sec. 7.1):
+    every work item is a handful of key tiles long, so the fixed cost of a work item shows."""
+    w = W.custom_workload("causal_short", [seq_len] * (tokens // seq_len), 1024, 32, 8, 128, "bf16", W.MaskSpec("causal"), seed=109,
+                          input_scale=1.0 / np.sqrt(128))
+    table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+    pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, table, w.ranges).sum())
+    q, k, v, do = gen_tensors(torch, w, 109)
+    plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)
+    out = torch.empty_like(q)
+    lse = torch.empty((w.hq, w.total_tokens), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(plan, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
+
+    def step():
+        P.dcp_block_attn_fwd(plan, q, k, v, out, lse, w.softmax_scale, None)
+        P.dcp_block_attn_bwd(plan, q, k, v, out, lse, do, dq, dk, dv, w.softmax_scale, ws, None)
+
+    step()
+    torch.cuda.synchronize()
+    P.dcp_profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    unit = pairs * w.hq * w.d
+    res = dict(workload=f"{tokens} tokens in {tokens // seq_len} causal sequences of {seq_len}, {w.hq}/{w.hkv} heads, D {w.d}",
+               visible_pairs=pairs, ms_per_step=round(ms, 4), tflops=round(14 * unit / (ms * 1e-3) / 1e12, 1))
+    for name, f in (("fwd", 4), ("dq", 4), ("dkv", 6)):
+        tot, n = P.dcp_profile_read(name)
+        res[name + "_ms"] = round(tot / max(n, 1), 4)
+        res[name + "_tflops"] = round(f * unit / (tot / max(n, 1) * 1e-3) / 1e12, 1)
+    P.dcp_profile_enable(False)
     return res
 
 
