@@ -244,6 +244,20 @@ size_t dcp_bwd_workspace_bytes(const dcp_plan_t* plan, int32_t hq, int32_t hkv, 
 dcp_status_t dcp_block_attn_bwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace,
                                 size_t workspace_bytes, void* stream);
 
+/* dcp_block_attn_bwd for callers that cannot allocate device memory or pass a workspace (code that runs under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and results, with the
+ * workspace in a fixed device array of DCP_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on.
+ * The call allocates nothing and does not synchronise.  Conditions:
+ *   - dcp_plan_prepare(plan, hq, hkv, d, dtype, impl, ...) has been called for this plan and shape on this device
+ *     (DCP_ERR_INVALID_ARG otherwise: the call will not create the plan's device copies itself);
+ *   - dcp_bwd_workspace_bytes(plan, hq, hkv, d, dtype) <= DCP_STATIC_SCRATCH_BYTES (DCP_ERR_WORKSPACE otherwise, with
+ *     both figures in the message; e.g. 32 query heads x 131 072 rows need 32 MiB plus the parts of cut dK/dV items);
+ *   - per-kernel timing (dcp_profile_enable) does not cover this call.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (two streams, two threads)
+ * race; calls ordered on one stream do not.  Inputs, outputs and errors otherwise as dcp_block_attn_bwd. */
+#define DCP_STATIC_SCRATCH_BYTES (64u << 20)
+dcp_status_t dcp_block_attn_bwd_static(dcp_plan_t* plan, const dcp_tensors_t* t, void* stream);
+
 /* Gradient reduction across blocks (Sec. 5 "Blockwise Reduction" used on gradients, Sec. 7.5):
  * dst[i] = sum_p parts[p][i], accumulated in fp32, stored as dst_dtype.
  *   parts_host_array_of_device_ptrs  host array of n_parts (1..8) device pointers, read during the

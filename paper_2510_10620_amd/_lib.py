@@ -70,6 +70,7 @@ _SIGS = {
     "dcp_bwd_delta": (ctypes.c_int, [ctypes.POINTER(Tensors), ctypes.c_int64, vp, vp]),
     "dcp_bwd_workspace_bytes": (ctypes.c_size_t, [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]),
     "dcp_block_attn_bwd": (ctypes.c_int, [vp, ctypes.POINTER(Tensors), vp, ctypes.c_size_t, vp]),
+    "dcp_block_attn_bwd_static": (ctypes.c_int, [vp, ctypes.POINTER(Tensors), vp]),
     "dcp_sum_partials": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int64, vp]),
     "dcp_copy_list_create": (ctypes.c_int, [ctypes.POINTER(vp), i32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]),
     "dcp_copy_list_destroy": (ctypes.c_int, [vp]),

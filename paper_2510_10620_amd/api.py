@@ -253,6 +253,18 @@ def dcp_block_attn_bwd(plan, q, k, v, out, lse, dout, dq, dk, dv, softmax_scale,
                                           workspace.numel() * workspace.element_size(), _stream()))
 
 
+DCP_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def dcp_block_attn_bwd_static(plan, q, k, v, out, lse, dout, dq, dk, dv, softmax_scale, attn_ranges=None, impl=DCP_IMPL_AUTO):
+    """dcp_block_attn_bwd without a workspace argument and without any allocation (the plan must have been prepared)."""
+    ts = _descr(q, k, v, softmax_scale, attn_ranges, impl)
+    for name, t in (("out", out), ("dout", dout), ("dq", dq), ("dk", dk), ("dv", dv)):
+        _set(ts, name, t)
+    ts.lse = lse.data_ptr()
+    _check(_lib.load().dcp_block_attn_bwd_static(plan.handle, ctypes.byref(ts), _stream()))
+
+
 def dcp_sum_partials(parts, dst):
     arr = (ctypes.c_void_p * len(parts))(*[p.data_ptr() for p in parts])
     _check(_lib.load().dcp_sum_partials(arr, len(parts), _dtype_code(parts[0]), dst.data_ptr(), _dtype_code(dst),

@@ -118,6 +118,8 @@ extern "C" dcp_status_t dcp_plan_prepare(dcp_plan_t* plan, int32_t hq, int32_t h
   if ((st = pick_impl(&t, &use_mfma)) != DCP_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   if ((st = plan->ensure_device(s)) != DCP_OK) return st;
+  void* scratch_addr = nullptr;   // looked up here so that dcp_block_attn_bwd_static finds it ready
+  if ((st = static_scratch(&scratch_addr)) != DCP_OK) return st;
   if (plan->total_tokens == 0) return DCP_OK;
   DevGroup g;
   if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g)) != DCP_OK) return st;

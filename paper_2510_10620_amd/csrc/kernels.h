@@ -51,6 +51,10 @@ struct ProfScope {
 dcp_status_t bwd_launch(dcp_plan_t* plan, const dcp_tensors_t* t, void* workspace, size_t workspace_bytes, hipStream_t s,
                         bool may_alloc);
 
+// device address, on the current device, of the fixed workspace of dcp_block_attn_bwd_static (bwd_static.hip); the first
+// call on a device looks it up
+dcp_status_t static_scratch(void** ptr);
+
 // scalar fp32-ALU family (any dtype; D in {32, 64, 128})
 bool scalar_supports(int32_t d);
 int scalar_fwd_tile();
