@@ -113,6 +113,7 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--only-stream", action="store_true", help="print only the share (merge) and Blockwise Copy sections")
     ap.add_argument("--only-short", type=int, default=0, help="print only the short-sequence section for this sequence length")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -129,6 +130,26 @@ def main():
         print(json.dumps(short_section(torch, P, W, np, steps=5, seq_len=args.only_short)))
         return
     w = W.make_workload(args.config)
+    if args.only_stream:
+        table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
+        q = gen_tensors(torch, w, w.tensor_seed)[0]
+        plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)
+        out_, do_ = torch.randn_like(q), torch.randn_like(q)
+        dbuf = torch.empty((w.hq, w.total_tokens), dtype=torch.float32, device="cuda")
+        P.dcp_bwd_delta(out_, do_, dbuf)
+        torch.cuda.synchronize()
+        P.dcp_profile_enable(True)
+        for _ in range(10):
+            P.dcp_bwd_delta(out_, do_, dbuf)
+        torch.cuda.synchronize()
+        tot, n = P.dcp_profile_read("delta")
+        P.dcp_profile_enable(False)
+        dgb = w.total_tokens * w.hq * (4 * w.d + 4) / (tot / n * 1e-3) / 1e9
+        print(json.dumps(dict(share=share_section(torch, P, W, np, steps=5, warmup=2),
+                              blockwise_copy=copy_section(torch, P, np, plan, q, steps=10),
+                              gradient_sum=sum_section(torch, P, q, steps=10),
+                              delta=dict(ms=round(tot / n, 4), GBps=round(dgb, 1), frac_hbm=round(dgb / PEAK_HBM_GBPS, 3)))))
+        return
     table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
     pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, table, w.ranges).sum())
     q, k, v, do = gen_tensors(torch, w, w.tensor_seed)
@@ -206,6 +227,7 @@ def main():
     if not args.no_extra:
         extra["share"] = share_section(torch, P, W, np, steps=max(3, args.steps // 4), warmup=2)
         extra["blockwise_copy"] = copy_section(torch, P, np, plan, q, steps=max(3, args.steps // 2))
+        extra["gradient_sum"] = sum_section(torch, P, q, steps=max(3, args.steps // 2))
         extra["short_sequences"] = short_section(torch, P, W, np, steps=5)
         extra["other_masks"] = masks_section(torch, P, W, np, steps=3)
         extra["execution_plan"] = executor_section(torch, P, W, np, steps=3)
@@ -288,6 +310,31 @@ def share_section(torch, P, W, np, steps, warmup):
         res[name + "_ms"] = round(tot / max(n, 1), 4)
     res["merge_GBps"] = round(merge_bytes / (res["merge_ms"] * 1e-3) / 1e9, 1)
     res["merge_frac_hbm"] = round(res["merge_GBps"] / PEAK_HBM_GBPS, 3)
+    n_parts = np.diff(mptr)
+    res["merge_rows_by_partials"] = {int(k): int(blk_len[n_parts == k].sum()) for k in np.unique(n_parts)}
+    del o_part, lse_part, plan
+    # the merge where every q block really has partials to merge: the WHOLE causal table of the same batch executed as
+    # 4 divisions (each q block's rows dealt to 4 slots), forward into the slots, then the merge alone
+    slot4, n_slots4, _ = W.deal_divisions(table[:, 0], n_div, div_seed)
+    plan4 = P.dcp_plan_create(w.cu_seqlens, w.block_size, table, slot4, n_slots4)
+    o4 = torch.empty((n_slots4, w.block_size, w.hq, w.d), dtype=torch.bfloat16, device="cuda")
+    l4 = torch.empty((n_slots4, w.hq, w.block_size), dtype=torch.float32, device="cuda")
+    P.dcp_block_attn_fwd(plan4, q, k, v, o4, l4, w.softmax_scale, rg)
+    P.dcp_merge_partials(plan4, o4, l4, out, lse)
+    torch.cuda.synchronize()
+    P.dcp_profile_enable(True)
+    for _ in range(steps):
+        P.dcp_merge_partials(plan4, o4, l4, out, lse)
+    torch.cuda.synchronize()
+    tot, n = P.dcp_profile_read("merge")
+    P.dcp_profile_enable(False)
+    mptr4 = plan4.export("MERGE_PTR").astype(np.int64)
+    bytes4 = int((blk_len * (np.diff(mptr4) + 1)).sum()) * rowhead
+    ms4 = tot / max(n, 1)
+    res["merge_whole_table"] = dict(workload=f"the whole {len(table)}-row table as {n_div} divisions -> {n_slots4} partial slots",
+                                    rows_by_partials={int(kk): int(blk_len[np.diff(mptr4) == kk].sum()) for kk in np.unique(np.diff(mptr4))},
+                                    ms=round(ms4, 4), GBps=round(bytes4 / (ms4 * 1e-3) / 1e9, 1),
+                                    frac_hbm=round(bytes4 / (ms4 * 1e-3) / 1e9 / PEAK_HBM_GBPS, 3))
     return res
 
 
@@ -439,6 +486,24 @@ def short_section(torch, P, W, np, steps, seq_len=1024, tokens=65536):
         res[name + "_tflops"] = round(f * unit / (tot / max(n, 1) * 1e-3) / 1e12, 1)
     P.dcp_profile_enable(False)
     return res
+
+
+def sum_section(torch, P, q, steps):
+    """Blockwise Reduction used on gradients: two bf16 partials of the size of dQ summed into a third tensor
+    (fp32 accumulation): algorithmic bytes = two reads + one write of every element."""
+    a, b, dst = torch.ones_like(q), torch.ones_like(q), torch.empty_like(q)
+    P.dcp_sum_partials([a, b], dst)
+    torch.cuda.synchronize()
+    P.dcp_profile_enable(True)
+    for _ in range(steps):
+        P.dcp_sum_partials([a, b], dst)
+    torch.cuda.synchronize()
+    tot, n = P.dcp_profile_read("sum")
+    P.dcp_profile_enable(False)
+    ms = tot / max(n, 1)
+    gbps = 3 * q.numel() * q.element_size() / (ms * 1e-3) / 1e9
+    return dict(workload=f"2 bf16 partials of {q.numel()} elements -> bf16", ms=round(ms, 4), GBps=round(gbps, 1),
+                frac_hbm=round(gbps / PEAK_HBM_GBPS, 3))
 
 
 def copy_section(torch, P, np, plan, q, steps):
