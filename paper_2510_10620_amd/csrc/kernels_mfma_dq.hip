@@ -207,8 +207,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
 #pragma unroll
     for (int a = 0; a < 4; a++) {
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(st.dq[dt][4 * a] * t.scale) | ((uint32_t)f32_to_bf16(st.dq[dt][4 * a + 1] * t.scale) << 16);
-      pk.y = (uint32_t)f32_to_bf16(st.dq[dt][4 * a + 2] * t.scale) | ((uint32_t)f32_to_bf16(st.dq[dt][4 * a + 3] * t.scale) << 16);
+      pk.x = pack_bf16x2(st.dq[dt][4 * a] * t.scale, st.dq[dt][4 * a + 1] * t.scale);
+      pk.y = pack_bf16x2(st.dq[dt][4 * a + 2] * t.scale, st.dq[dt][4 * a + 3] * t.scale);
       *(uint2*)(op + 32 * dt + 8 * a + 4 * lh) = pk;
     }
 }

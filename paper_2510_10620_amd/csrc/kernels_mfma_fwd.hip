@@ -464,8 +464,8 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
 #pragma unroll
       for (int a = 0; a < 4; a++) {
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(st.o[nq][dt][4 * a] * inv) | ((uint32_t)f32_to_bf16(st.o[nq][dt][4 * a + 1] * inv) << 16);
-        pk.y = (uint32_t)f32_to_bf16(st.o[nq][dt][4 * a + 2] * inv) | ((uint32_t)f32_to_bf16(st.o[nq][dt][4 * a + 3] * inv) << 16);
+        pk.x = pack_bf16x2(st.o[nq][dt][4 * a] * inv, st.o[nq][dt][4 * a + 1] * inv);
+        pk.y = pack_bf16x2(st.o[nq][dt][4 * a + 2] * inv, st.o[nq][dt][4 * a + 3] * inv);
         *(uint2*)(op + 32 * dt + 8 * a + 4 * lh) = pk;
       }
   }

@@ -352,10 +352,10 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
 #pragma unroll
     for (int a = 0; a < 4; a++) {
       uint2 pk, pv;
-      pk.x = (uint32_t)f32_to_bf16(st.dk[dt][4 * a] * t.scale) | ((uint32_t)f32_to_bf16(st.dk[dt][4 * a + 1] * t.scale) << 16);
-      pk.y = (uint32_t)f32_to_bf16(st.dk[dt][4 * a + 2] * t.scale) | ((uint32_t)f32_to_bf16(st.dk[dt][4 * a + 3] * t.scale) << 16);
-      pv.x = (uint32_t)f32_to_bf16(st.dv[dt][4 * a]) | ((uint32_t)f32_to_bf16(st.dv[dt][4 * a + 1]) << 16);
-      pv.y = (uint32_t)f32_to_bf16(st.dv[dt][4 * a + 2]) | ((uint32_t)f32_to_bf16(st.dv[dt][4 * a + 3]) << 16);
+      pk.x = pack_bf16x2(st.dk[dt][4 * a] * t.scale, st.dk[dt][4 * a + 1] * t.scale);
+      pk.y = pack_bf16x2(st.dk[dt][4 * a + 2] * t.scale, st.dk[dt][4 * a + 3] * t.scale);
+      pv.x = pack_bf16x2(st.dv[dt][4 * a], st.dv[dt][4 * a + 1]);
+      pv.y = pack_bf16x2(st.dv[dt][4 * a + 2], st.dv[dt][4 * a + 3]);
       *(uint2*)(dkp + 32 * dt + 8 * a + 4 * lh) = pk;
       *(uint2*)(dvp + 32 * dt + 8 * a + 4 * lh) = pv;
     }

@@ -562,7 +562,6 @@ static int64_t tile_cost(int32_t kind, int64_t r0, int64_t r1, int64_t c0, int64
 // Workgroups the chip holds at once in the kernels that split their items (2 per CU, 256 CUs).
 static constexpr int64_t kResidentWorkgroups = 512;
 static constexpr int32_t kMaxParts = 64;
-static constexpr int kCostClasses = 4;
 
 const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
   std::lock_guard<std::mutex> lock(mu);
@@ -659,20 +658,11 @@ const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
     }
   }
   std::stable_sort(sc.begin(), sc.end(), [](const Scored& a, const Scored& b) { return a.cost > b.cost; });
-  if (gid == 2 && !sc.empty() && sc[0].cost > 0) {
-    // dK/dV: longest first only coarsely -- kCostClasses classes of cost -- and sequence by sequence inside a class.
-    // The key tiles of one sequence that run at the same time then stream the same Q / dO rows (each walks its
-    // query tiles from the last one down), which the L2 of their XCD serves once.  Measured on the 65 536-token
-    // causal batch: 13.9 -> 9.0 GB fetched per launch (8.8 -> 5.5 times the algorithmic bytes), same time; whole
-    // sequences kept together (one class) fetch 7.5 GB but lose the balance on batches of equal sequences.
-    const int64_t top = sc[0].cost;
-    auto cls = [&](const Scored& x) { return (int)std::min<int64_t>(kCostClasses - 1, x.cost * kCostClasses / top); };
-    std::stable_sort(sc.begin(), sc.end(), [&](const Scored& a, const Scored& b) {
-      const int ca = cls(a), cb = cls(b);
-      if (ca != cb) return ca > cb;
-      return blk_seq[hg->unit_blk[a.w.unit]] < blk_seq[hg->unit_blk[b.w.unit]];
-    });
-  }
+  // (Longest first is kept strict.  Grouping the dK/dV items of one sequence -- longest first only by four classes of
+  // length, sequence by sequence inside a class -- makes the key tiles that run together stream the same Q / dO rows and
+  // cuts the launch's fetched bytes from 13.9 to 9.0 GB on the 65 536-token causal batch, 7.5 GB with whole sequences
+  // kept together, but the launch is no faster for it: 0.8 % slower with four or eight classes, from the looser
+  // balance, and batches of equal sequences lose much more.)
   hi.items.resize(sc.size());
   for (size_t i = 0; i < sc.size(); i++) hi.items[i] = sc[i].w;
   return h_items.emplace(key, std::move(hi)).first->second;
