@@ -177,7 +177,8 @@ dcp_status_t dcp_plan_export(const dcp_plan_t* plan, dcp_export_t which, int32_t
  * [e0, e1) the piece covers, pslot).  An item that would keep one workgroup busy much longer than its
  * share of the launch is cut along its table rows into parts; each part has its own pslot >= 0 (a slot
  * of fp32 partial sums in the backward workspace, which a reduce kernel adds up in slot order) and
- * unsplit items have pslot -1.  Pieces are listed longest first.  dst_host may be NULL to query the
+ * unsplit items have pslot -1.  Pieces are listed in launch order (sequence by sequence when that balances as well as
+ * strict longest-first, else longest first).  dst_host may be NULL to query the
  * length; n_items_out receives the number of rows (5 int32 each).  Host only. */
 dcp_status_t dcp_plan_export_dkv_items(dcp_plan_t* plan, int32_t hkv, int32_t* dst_host, int64_t capacity_rows,
                                        int64_t* n_items_out);

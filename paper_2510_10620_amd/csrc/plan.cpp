@@ -658,11 +658,39 @@ const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
     }
   }
   std::stable_sort(sc.begin(), sc.end(), [](const Scored& a, const Scored& b) { return a.cost > b.cost; });
-  // (Longest first is kept strict.  Grouping the dK/dV items of one sequence -- longest first only by four classes of
-  // length, sequence by sequence inside a class -- makes the key tiles that run together stream the same Q / dO rows and
-  // cuts the launch's fetched bytes from 13.9 to 9.0 GB on the 65 536-token causal batch, 7.5 GB with whole sequences
-  // kept together, but the launch is no faster for it: 0.8 % slower with four or eight classes, from the looser
-  // balance, and batches of equal sequences lose much more.)
+  if (gid == 2 && split_heads > 0 && !sc.empty()) {
+    // dK/dV: sequence by sequence (the costliest sequence first, longest item first inside it) when that balances as
+    // well as strict longest-first does.  The key tiles of one sequence that run at the same time stream the same
+    // Q / dO rows (each walks its query tiles from the last one down), so their XCD's L2 serves those rows once:
+    // 13.9 -> 7.5 GB fetched per launch on the 65 536-token causal batch, and the step gains 1 % -- not in this kernel's
+    // own time but in the clock the chip grants its neighbours, its power being what is limited.  A batch of equal
+    // sequences balances badly in this order (every round of workgroups mixes long and short items), which the
+    // launch played through as list scheduling shows; it keeps strict longest-first.  (Longest-first by four or eight
+    // classes of length with sequences grouped inside a class was in between on traffic and 0.8 % slower; the same
+    // order for the forward and dQ lists changed nothing measurable.)
+    auto play = [&](const std::vector<Scored>& v) {
+      std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> slots;
+      for (int64_t i = 0; i < kResidentWorkgroups; i++) slots.push(0);
+      int64_t end = 0;
+      for (int h = 0; h < split_heads; h++)          // the grid runs the list once per head, head-major
+        for (const Scored& it : v) {
+          const int64_t t0 = slots.top();
+          slots.pop();
+          slots.push(t0 + it.cost);
+          end = std::max(end, t0 + it.cost);
+        }
+      return end;
+    };
+    std::vector<int64_t> seq_cost(n_seq, 0);
+    for (const Scored& x : sc) seq_cost[blk_seq[hg->unit_blk[x.w.unit]]] += x.cost;
+    std::vector<Scored> by_seq(sc);
+    std::stable_sort(by_seq.begin(), by_seq.end(), [&](const Scored& a, const Scored& b) {
+      const int32_t sa = blk_seq[hg->unit_blk[a.w.unit]], sb = blk_seq[hg->unit_blk[b.w.unit]];
+      if (sa == sb) return false;
+      return seq_cost[sa] != seq_cost[sb] ? seq_cost[sa] > seq_cost[sb] : sa < sb;
+    });
+    if ((double)play(by_seq) <= 1.01 * (double)play(sc)) sc.swap(by_seq);
+  }
   hi.items.resize(sc.size());
   for (size_t i = 0; i < sc.size(); i++) hi.items[i] = sc[i].w;
   return h_items.emplace(key, std::move(hi)).first->second;
