@@ -200,17 +200,10 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
     if (!have) break;
     step(stage1, stage0);
   }
-  if (!qv) return;
-  bf16_t* op = (bf16_t*)t.dq + (int64_t)(st.qi + qoff) * t.dq_st + (int64_t)head * t.dq_sh;
-#pragma unroll
-  for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-    for (int a = 0; a < 4; a++) {
-      uint2 pk;
-      pk.x = pack_bf16x2(st.dq[dt][4 * a] * t.scale, st.dq[dt][4 * a + 1] * t.scale);
-      pk.y = pack_bf16x2(st.dq[dt][4 * a + 2] * t.scale, st.dq[dt][4 * a + 3] * t.scale);
-      *(uint2*)(op + 32 * dt + 8 * a + 4 * lh) = pk;
-    }
+  // dQ goes out in whole rows, turned round through the tile stages (free after the last step's barrier)
+  static_assert(2 * 32 * kORow <= 2 * kTileBytes, "two waves stage their output tiles in one tile stage");
+  bf16_t* op = (bf16_t*)t.dq + (int64_t)(wq_lo + qoff) * t.dq_st + (int64_t)head * t.dq_sh;
+  store_tile32((wave < 2 ? stage0 : stage1) + (wave & 1) * (32 * kORow), st.dq, t.scale, lane, w_rows, op, t.dq_st);
 }
 
 int mfma_dq_tile() { return 128; }

@@ -442,32 +442,24 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
     step(stage1, stage0);
   }
 
-  // ---- epilogue: O = acc / l, LSE = ln2 * (m c + log2 l)
+  // ---- epilogue: O = acc / l, LSE = ln2 * (m c + log2 l); the output tile goes out in whole rows (the tile stages
+  // are free after the last step's barrier, two waves stage in each)
+  static_assert(2 * 32 * kORow <= 2 * kTileBytes, "two waves stage their output tiles in one tile stage");
+  char* ot = (wave < 2 ? stage0 : stage1) + (wave & 1) * (32 * kORow);
   const int slot = g.unit_out[w.unit];
 #pragma unroll
   for (int nq = 0; nq < NQ; nq++) {
     const float lt = xhalf_sum(st.l[nq]);
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const float lse = lt > 0.f ? (st.m[nq] * c_log2 + __builtin_amdgcn_logf(lt)) * 0.69314718055994530942f : -INFINITY;
-    if (!qv[nq]) continue;
-    const int row = row0 + wrow0 + nq * 32 + li;  // row inside the block
-    bf16_t* op;
-    if (slot < 0) {
-      op = (bf16_t*)t.out + (int64_t)(blk_start + row + qoff) * t.o_st + (int64_t)head * t.o_sh;
-      if (lh == 0) t.lse[(int64_t)head * t.q_rows + blk_start + row + qoff] = lse;
-    } else {
-      op = (bf16_t*)t.out + (((int64_t)slot * t.block_size + row) * t.hq + head) * kD;
-      if (lh == 0) t.lse[((int64_t)slot * t.hq + head) * t.block_size + row] = lse;
+    const int brow0 = row0 + wrow0 + nq * 32;   // the wave's first row inside the block
+    if (qv[nq] && lh == 0) {
+      if (slot < 0) t.lse[(int64_t)head * t.q_rows + blk_start + brow0 + li + qoff] = lse;
+      else t.lse[((int64_t)slot * t.hq + head) * t.block_size + brow0 + li] = lse;
     }
-#pragma unroll
-    for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-      for (int a = 0; a < 4; a++) {
-        uint2 pk;
-        pk.x = pack_bf16x2(st.o[nq][dt][4 * a] * inv, st.o[nq][dt][4 * a + 1] * inv);
-        pk.y = pack_bf16x2(st.o[nq][dt][4 * a + 2] * inv, st.o[nq][dt][4 * a + 3] * inv);
-        *(uint2*)(op + 32 * dt + 8 * a + 4 * lh) = pk;
-      }
+    bf16_t* op = slot < 0 ? (bf16_t*)t.out + (int64_t)(blk_start + brow0 + qoff) * t.o_st + (int64_t)head * t.o_sh
+                          : (bf16_t*)t.out + (((int64_t)slot * t.block_size + brow0) * t.hq + head) * kD;
+    store_tile32(ot, st.o[nq], inv, lane, n_rows - wrow0 - nq * 32, op, slot < 0 ? t.o_st : (int64_t)t.hq * kD);
   }
 }
 

@@ -294,6 +294,40 @@ __device__ __forceinline__ float xhalf_max(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
+// Writes a wave's 32 x 128 result tile to memory as bf16, turned round through LDS.
+// acc is the accumulator of a transposed product: lane (li, lh) holds row li of the tile in 8-byte pieces scattered
+// over the row (columns 32 dt + 8 a + 4 lh .. + 3 in acc[dt][4 a .. 4 a + 3]), so stored straight from the registers
+// every store instruction touches 32 rows with 16 bytes each.  Here the wave writes the pieces into a region of LDS
+// of its own (32 rows of kORow bytes at `ot`; no other wave may use it meanwhile, and no barrier between waves is
+// needed), reads them back as whole rows, and each store instruction writes four full 256-byte rows.
+// mul: factor of the lane's row.  Rows r < n_valid go to row0_ptr + r * stride (elements).
+static constexpr int kORow = kRowBytes + 16;   // staged row pitch: 16 bytes of padding spread the rows over the banks
+__device__ __forceinline__ void store_tile32(char* ot, const f32x16 (&acc)[4], float mul, int lane, int n_valid, bf16_t* row0_ptr,
+                                             int64_t stride) {
+  const int li = lane & 31, lh = lane >> 5, lr = lane >> 4, lc = lane & 15;
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+    for (int a = 0; a < 4; a++) {
+      uint2 pk;
+      pk.x = pack_bf16x2(acc[dt][4 * a] * mul, acc[dt][4 * a + 1] * mul);
+      pk.y = pack_bf16x2(acc[dt][4 * a + 2] * mul, acc[dt][4 * a + 3] * mul);
+      *(uint2*)(ot + li * kORow + 2 * (32 * dt + 8 * a + 4 * lh)) = pk;
+    }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    const int r = 4 * i + lr;
+    const uint4 piece = *(const uint4*)(ot + r * kORow + 16 * lc);
+    if (r < n_valid) *(uint4*)(row0_ptr + (int64_t)r * stride + 8 * lc) = piece;
+  }
+  // the next use of the region by this wave comes after these reads
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 __device__ __forceinline__ float xhalf_sum(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);

@@ -330,8 +330,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
     __syncthreads();
     buf ^= kStageBytes;
   }
-  if (!kvalid) return;
   if (w.pslot >= 0) {
+    if (!kvalid) return;
     // one part of a split item: the fp32 sums go to the part's slot, the reduce kernel adds the parts up
     float* pk = t.part + (((int64_t)w.pslot * t.hkv + hk) * 2 * TK + wrow0 + li) * 128 + 4 * lh;
     float* pv = pk + TK * 128;
@@ -345,20 +345,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
       }
     return;
   }
-  bf16_t* dkp = (bf16_t*)t.dk + (int64_t)(wk_lo + li + koff) * t.dk_st + (int64_t)hk * t.dk_sh;
-  bf16_t* dvp = (bf16_t*)t.dv + (int64_t)(wk_lo + li + koff) * t.dv_st + (int64_t)hk * t.dv_sh;
-#pragma unroll
-  for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-    for (int a = 0; a < 4; a++) {
-      uint2 pk, pv;
-      pk.x = pack_bf16x2(st.dk[dt][4 * a] * t.scale, st.dk[dt][4 * a + 1] * t.scale);
-      pk.y = pack_bf16x2(st.dk[dt][4 * a + 2] * t.scale, st.dk[dt][4 * a + 3] * t.scale);
-      pv.x = pack_bf16x2(st.dv[dt][4 * a], st.dv[dt][4 * a + 1]);
-      pv.y = pack_bf16x2(st.dv[dt][4 * a + 2], st.dv[dt][4 * a + 3]);
-      *(uint2*)(dkp + 32 * dt + 8 * a + 4 * lh) = pk;
-      *(uint2*)(dvp + 32 * dt + 8 * a + 4 * lh) = pv;
-    }
+  // dK and dV go out in whole rows, turned round through the stages (free after the last step's barrier), one
+  // region per wave, dK first and dV after it through the same region
+  static_assert(4 * 32 * kORow <= 2 * kStageBytes, "the four waves' output tiles fit in the stages");
+  char* ot = stages + wave * (32 * kORow);
+  store_tile32(ot, st.dk, t.scale, lane, w_rows, (bf16_t*)t.dk + (int64_t)(wk_lo + koff) * t.dk_st + (int64_t)hk * t.dk_sh, t.dk_st);
+  store_tile32(ot, st.dv, 1.f, lane, w_rows, (bf16_t*)t.dv + (int64_t)(wk_lo + koff) * t.dv_st + (int64_t)hk * t.dv_sh, t.dv_st);
 }
 
 }  // namespace dcp
