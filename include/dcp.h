@@ -143,7 +143,9 @@ dcp_status_t dcp_plan_destroy(dcp_plan_t* plan);
  * hq / hkv heads, on the device that is current.  This is the one place that allocates device memory (hipMalloc)
  * and waits for `stream` (the upload of the arrays); after it, dcp_block_attn_fwd, dcp_block_attn_bwd and
  * dcp_merge_partials with this plan and shape only enqueue kernels.  Without it the first of those calls does the same
- * work itself, once.  Call it after dcp_plan_set_block_buffers, if that is used.  Errors as for the launching calls. */
+ * work itself, once.  Call it after dcp_plan_set_block_buffers, if that is used.  Errors as for the launching calls.
+ * A prepared plan's launches are kernel launches and nothing else (no memset or copy nodes, no events), so they may
+ * be recorded into a HIP graph by stream capture and replayed. */
 dcp_status_t dcp_plan_prepare(dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype, int32_t impl,
                               void* stream);
 

@@ -567,6 +567,45 @@ def test_two_runs_are_bit_identical():
                                runs[1][n].view(torch.int16 if n != "lse" else torch.int32)), f"{label}: {n} differs between two runs"
 
 
+def test_step_replays_from_a_hip_graph():
+    """With a prepared plan the forward, the merge and the backward only launch kernels (no allocation, no
+    synchronisation, no memset node), so a caller can record the step in a HIP graph.  Recorded once here, on a case
+    with partial output slots and cut dK/dV items, then replayed three times with eager work and a synchronisation
+    between the replays; every replay must give the bits of the eager run."""
+    import torch
+    import paper_2510_10620_amd as P
+    lens = W.draw_lengths(8192, "lognormal", 512, 4096, seed=2, median=1024)
+    w = W.custom_workload("graph", lens, 256, 8, 2, 128, "bf16", W.MaskSpec("causal"), seed=57, input_scale=1.0 / np.sqrt(128))
+    tensors = W.make_tensors(w)
+    table = H.oracle_table(w)
+    slot, n_slots, _ = W.deal_divisions(table[:, 0], 3, 58)
+    g = H.GpuRun(w, tensors, table, slot, n_slots)
+    P.dcp_plan_prepare(g.plan, w.hq, w.hkv, w.d, P.DCP_BF16)
+    g.forward_only()
+    g.backward_only(g.out, g.lse)
+    ref = {n: getattr(g, n).clone() for n in ALL}
+    bufs = {n: torch.full_like(ref[n], float("nan")) for n in ALL}
+    o_part, lse_part = torch.full_like(g.o_part, float("nan")), torch.full_like(g.lse_part, float("nan"))
+    ws = torch.empty(max(256, P.dcp_bwd_workspace_bytes(g.plan, w.hq, w.hkv, w.d, P.DCP_BF16)), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        P.dcp_block_attn_fwd(g.plan, g.q, g.k, g.v, o_part, lse_part, w.softmax_scale, g.ranges)
+        P.dcp_merge_partials(g.plan, o_part, lse_part, bufs["out"], bufs["lse"])
+        P.dcp_block_attn_bwd(g.plan, g.q, g.k, g.v, bufs["out"], bufs["lse"], g.dout, bufs["dq"], bufs["dk"], bufs["dv"],
+                             w.softmax_scale, ws, g.ranges)
+    for rep in range(3):
+        for t in list(bufs.values()) + [o_part, lse_part]:
+            t.fill_(float("nan"))                      # eager work between the replays
+        ws.random_(0, 255)                             # the partial sums of the last replay are no input of the next
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in ALL:
+            assert torch.equal(bufs[n].view(torch.int16 if n != "lse" else torch.int32),
+                               ref[n].view(torch.int16 if n != "lse" else torch.int32)), f"replay {rep}: {n} differs from the eager run"
+
+
 def test_execution_plan_inline_copy_and_gradient_sum():
     """The two instruction types the division test does not use: an in-line Blockwise Copy (it runs on the compute
     stream, in order) that fills the K / V tensors the attention then reads, and Blockwise Reduction used on gradients
