@@ -96,7 +96,6 @@ static KTensors pack(const dcp_plan_t* plan, const dcp_tensors_t* t) {
   k.sink = plan->has_window ? plan->sink : 0;
   k.masked = (plan->has_ranges || plan->has_window) ? 1 : 0;
   k.qbounds = nullptr;
-  k.work_ctr = nullptr;
   k.q_st = t->q_stride_t; k.q_sh = t->q_stride_h; k.k_st = t->k_stride_t; k.k_sh = t->k_stride_h;
   k.v_st = t->v_stride_t; k.v_sh = t->v_stride_h; k.o_st = t->o_stride_t; k.o_sh = t->o_stride_h;
   k.do_st = t->do_stride_t; k.do_sh = t->do_stride_h; k.dq_st = t->dq_stride_t; k.dq_sh = t->dq_stride_h;
@@ -186,11 +185,10 @@ extern "C" dcp_status_t dcp_bwd_delta(const dcp_tensors_t* t, int64_t total_toke
                       nullptr, total_tokens, t->hq, t->d, t->dtype, (hipStream_t)stream);
 }
 
-// Workspace layout: delta [Hq, rows] | lse2 [Hq, rows] | range-bound summaries | work-queue counters |
-// partial dK / dV sums of split items.
+// Workspace layout: delta [Hq, rows] | lse2 [Hq, rows] | range-bound summaries | partial dK / dV sums of split items.
 struct BwdWorkspace {
-  size_t n_hT, n_bounds, n_ctr, n_part;
-  size_t total() const { return 2 * n_hT + n_bounds + n_ctr + n_part; }
+  size_t n_hT, n_bounds, n_part;
+  size_t total() const { return 2 * n_hT + n_bounds + n_part; }
 };
 
 static BwdWorkspace bwd_workspace(dcp_plan_t* plan, int32_t hq, int32_t hkv, int32_t d, int32_t dtype) {
@@ -200,10 +198,7 @@ static BwdWorkspace bwd_workspace(dcp_plan_t* plan, int32_t hq, int32_t hkv, int
   // range-bound summaries of every 32-row tile (+1 spare entry), only for tables with RANGES or WINDOW rows
   w.n_bounds = (plan->has_ranges || plan->has_window) ? ((size_t)plan->blk_t32.back() + 1) * 8 * sizeof(int32_t) : 0;
   w.n_bounds = (w.n_bounds + 255) & ~(size_t)255;
-  if (hkv > 0 && mfma_supports(dtype, d)) {
-    w.n_ctr = (kWorkCtrInts * sizeof(uint32_t) + 255) & ~(size_t)255;
-    w.n_part = mfma_dkv_part_bytes(plan->host_items(2, mfma_dkv_tile(), hkv).n_pslots, hkv);
-  }
+  if (hkv > 0 && mfma_supports(dtype, d)) w.n_part = mfma_dkv_part_bytes(plan->host_items(2, mfma_dkv_tile(), hkv).n_pslots, hkv);
   return w;
 }
 
@@ -259,8 +254,7 @@ dcp_status_t dcp::bwd_launch(dcp_plan_t* plan, const dcp_tensors_t* t, void* wor
   if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv, use_mfma ? t->hkv : 0, may_alloc)) != DCP_OK) return st;
   KTensors k = pack(plan, t);
   const size_t n_hT = wsz.n_hT;
-  k.work_ctr = wsz.n_ctr ? (uint32_t*)((char*)workspace + 2 * wsz.n_hT + wsz.n_bounds) : nullptr;
-  k.part = (float*)((char*)workspace + 2 * wsz.n_hT + wsz.n_bounds + wsz.n_ctr);
+  k.part = (float*)((char*)workspace + 2 * wsz.n_hT + wsz.n_bounds);
   float* delta = (float*)workspace;
   float* lse2 = (float*)((char*)workspace + n_hT);
   k.delta = delta;

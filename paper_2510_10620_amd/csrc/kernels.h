@@ -4,9 +4,6 @@
 
 namespace dcp {
 
-// Counters of the per-XCD work queues (claim_work in mfma_common.h): one per XCD, a cache line apart.
-static constexpr int kWorkCtrInts = 8 * 16;
-
 // Plain-old-data copy of the caller's tensor descriptor plus derived fields, passed by value.
 struct KTensors {
   const void *q, *k, *v, *dout, *out_in;
@@ -21,7 +18,6 @@ struct KTensors {
   int32_t masked;          // the table has RANGES or WINDOW rows (rows with per-token ranges)
   float* part;             // backward, or null: fp32 partial sums of split dK/dV items, [slot][KV head][dK, dV][128 keys][D]
   const int32_t* qbounds;  // backward, or null: [32-row tiles of all blocks + 1][8] bounds of the rows' ranges (RangeBounds order)
-  uint32_t* work_ctr;      // backward, MFMA family: kWorkCtrInts counters of the dK/dV kernel's per-XCD work queues (claim_work)
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh, dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
   int64_t q_rows;   // rows of the Q-type buffers (= packed tokens without block buffers): row pitch of lse / delta / lse2
   int32_t hq, hkv, d, block_size;

@@ -68,26 +68,11 @@ dcp_status_t mfma_range_bounds(const DevGroup& g, const KTensors& t, const int32
 
 int mfma_dkv_tile() { return 128; }
 
-// zeroes the counters of the work queues (a kernel rather than a memset, so that the launch sequence can be recorded
-// in a graph as kernel nodes only)
-__global__ void work_reset_kernel(uint32_t* ctr) {
-  if (threadIdx.x < kWorkCtrInts) ctr[threadIdx.x] = 0;
-}
-
-// Workgroups of a launch that takes its work through claim_work: a quarter more per XCD than its eighth of the
-// work, so that an XCD running up to 25 % faster than the slowest still has workgroups to take work with.
-static int work_grid(int total) {
-  const int per_xcd = (total + 7) / 8;
-  return 8 * (per_xcd + (per_xcd + 3) / 4);
-}
-
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
-  if (!t.work_ctr) return fail(DCP_ERR_INVALID_ARG, "the dK/dV kernel needs the work counters of the backward workspace");
-  const int grid = work_grid(g.n_items * t.hkv);
-  hipLaunchKernelGGL(work_reset_kernel, dim3(1), dim3(kWorkCtrInts), 0, s, t.work_ctr);
-  if (t.masked) mfma_dkv_launch_ranges(g, t, grid, s);   // the variant for per-token ranges lives in its own file
-  else hipLaunchKernelGGL(mfma_dkv_kernel<false>, dim3(grid), dim3(256), 0, s, g, t);
+  const int per_xcd = (g.n_items * t.hkv + 7) / 8;
+  if (t.masked) mfma_dkv_launch_ranges(g, t, per_xcd * 8, s);   // the variant for per-token ranges lives in its own file
+  else hipLaunchKernelGGL(mfma_dkv_kernel<false>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   if (g.n_reduce > 0) {
     hipLaunchKernelGGL(dkv_reduce_kernel, dim3(g.n_reduce, t.hkv), dim3(256), 0, s, g, t);

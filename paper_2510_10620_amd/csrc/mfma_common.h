@@ -395,31 +395,4 @@ __device__ __forceinline__ bool decode_wg(int n_items, int heads_outer, int head
   return true;
 }
 
-// Work order with queues: the same 8 contiguous chunks of the work order, one per XCD, but a workgroup takes the next
-// position of its XCD's chunk from a counter instead of from its own id, and when that chunk is used up it takes from
-// the chunks of the other XCDs.  The XCDs of one chip do not run at one clock (1.70 to 1.86 GHz were measured side by
-// side in one launch), and the hardware deals workgroup ids to them round-robin whatever their pace: with the chunk
-// bound to the id the launch ends when the slowest XCD has done its eighth.  The grid holds more workgroups than
-// work (work_grid): the surplus ones of a fast XCD are what takes over a slow XCD's work; one that finds every chunk
-// used up returns.  Which workgroup does a piece of work has no influence on the results.
-// ctr: kWorkCtrInts zeroed counters; bcast: one int of LDS.  Every thread of the workgroup must call it (barrier
-// inside); returns the position in the work order, wave-uniform, or -1.
-__device__ __forceinline__ int claim_work(uint32_t* ctr, int total, int* bcast) {
-  const int per_xcd = (total + 7) >> 3;
-  if (threadIdx.x == 0) {
-    const int home = blockIdx.x & 7;
-    int w = -1;
-    for (int k = 0; k < 8 && w < 0; k++) {
-      const int v = (home + k) & 7;
-      const int len = min(per_xcd, total - v * per_xcd);
-      if (len <= 0) continue;
-      const uint32_t i = atomicAdd(&ctr[v * 16], 1u);
-      if (i < (uint32_t)len) w = v * per_xcd + (int)i;
-    }
-    *bcast = w;
-  }
-  __syncthreads();
-  return __builtin_amdgcn_readfirstlane(*bcast);
-}
-
 }  // namespace dcp

@@ -235,11 +235,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
   constexpr int TK = 128;
   __shared__ __attribute__((aligned(1024))) char stages[2 * kStageBytes];   // double buffer
 
-  // position in the work order (kv head major, then item) from the XCD's queue
-  __shared__ int claimed;
-  const int wpos = claim_work(t.work_ctr, g.n_items * t.hkv, &claimed);
-  if (wpos < 0) return;
-  const int item = wpos % g.n_items, hk = wpos / g.n_items;
+  int item, hk;
+  if (!decode_wg(g.n_items, t.hkv, 1, &item, &hk)) return;
   const int G = t.hq / t.hkv;
   WorkItem w = g.items[item];
   w.unit = uni(w.unit); w.tile = uni(w.tile); w.e0 = uni(w.e0); w.e1 = uni(w.e1); w.pslot = uni(w.pslot);

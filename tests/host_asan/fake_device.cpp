@@ -107,9 +107,6 @@ dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t) {
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t) {
   dcp_status_t st = walk_group(g, 128, g_fake_kv_rows, t.q_rows, 0, t.block_size, true);
   if (st != DCP_OK) return st;
-  // the work-queue counters lie inside the workspace
-  WALK_CHECK(t.work_ctr != nullptr, "no work counters");
-  for (int i = 0; i < kWorkCtrInts; i++) t.work_ctr[i] = 0;
   // every part slot of a cut item lies inside the partial-sum area of the workspace: touch its last float
   for (int32_t i = 0; i < g.n_items; i++)
     if (g.items[i].pslot >= 0) t.part[((int64_t)(g.items[i].pslot + 1) * t.hkv) * 2 * 128 * 128 - 1] = 0.f;

@@ -154,10 +154,10 @@ def test_dkv_work_list_is_an_exact_partition(spec, lens, B, hkv):
         assert n_split > 0            # the long items of these workloads are cut
     else:
         assert n_split == 0
-    # the workspace grows by the partial sums (2 x 128 x 128 fp32 per slot and KV head) and by 512 bytes of work counters
+    # the workspace grows by the partial sums: 2 x 128 x 128 fp32 per slot and KV head
     base = P.dcp_bwd_workspace_bytes(plan, 4 * hkv, hkv, 64, P.DCP_BF16)       # D = 64: scalar kernels, no partial sums
     full = P.dcp_bwd_workspace_bytes(plan, 4 * hkv, hkv, 128, P.DCP_BF16)
-    assert full - base == len(slots) * hkv * 2 * 128 * 128 * 4 + 512      # + the counters of the kernel's work queues
+    assert full - base == len(slots) * hkv * 2 * 128 * 128 * 4
 
 
 @pytest.mark.parametrize("window,sink", [(50, 0), (40, 7), (16, 16), (1, 0), (300, 3), (5, 400)])
