@@ -185,6 +185,14 @@ dcp_status_t dcp_plan_export(const dcp_plan_t* plan, dcp_export_t which, int32_t
 dcp_status_t dcp_plan_export_dkv_items(dcp_plan_t* plan, int32_t hkv, int32_t* dst_host, int64_t capacity_rows,
                                        int64_t* n_items_out);
 
+/* How the list above is divided among the 8 XCDs of the chip, for host checks.  Workgroup ids go to the XCDs
+ * round-robin, and the kernels give XCD x a fixed eighth of the work: whole KV heads when hkv is a multiple of 8.
+ * Otherwise the list is dealt into n_seg = 8 / gcd(8, hkv) segments of about equal cost (sequences whole, except
+ * those that are more than half a segment by themselves), the order inside a segment kept, and an XCD takes (KV head,
+ * segment) pairs.  seg_out receives 9 numbers: segment s is rows [seg[s], seg[s + 1]) of dcp_plan_export_dkv_items'
+ * list, entries past n_seg repeat the list length.  The forward and dQ lists are divided the same way.  Host only. */
+dcp_status_t dcp_plan_export_dkv_segments(dcp_plan_t* plan, int32_t hkv, int32_t* n_seg_out, int32_t* seg_out);
+
 /* ---------------------------------------------------------------------------------------------
  * Tensor descriptor shared by the launching calls.  Unused members are NULL / 0. */
 typedef struct {

@@ -65,6 +65,7 @@ _SIGS = {
     "dcp_plan_prepare": (ctypes.c_int, [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]),
     "dcp_plan_export": (ctypes.c_int, [vp, ctypes.c_int, i32p, ctypes.c_int64, i64p]),
     "dcp_plan_export_dkv_items": (ctypes.c_int, [vp, ctypes.c_int32, i32p, ctypes.c_int64, i64p]),
+    "dcp_plan_export_dkv_segments": (ctypes.c_int, [vp, ctypes.c_int32, i32p, i32p]),
     "dcp_block_attn_fwd": (ctypes.c_int, [vp, ctypes.POINTER(Tensors), vp]),
     "dcp_merge_partials": (ctypes.c_int, [vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp]),
     "dcp_bwd_delta": (ctypes.c_int, [ctypes.POINTER(Tensors), ctypes.c_int64, vp, vp]),

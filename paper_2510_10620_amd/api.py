@@ -175,6 +175,15 @@ def dcp_plan_export_dkv_items(plan, hkv):
     return out
 
 
+def dcp_plan_export_dkv_segments(plan, hkv):
+    """(n_seg, seg[9]): how the dK/dV work list for `hkv` KV heads is divided among the XCDs."""
+    lib = _lib.load()
+    n = ctypes.c_int32(0)
+    seg = np.zeros(9, dtype=np.int32)
+    _check(lib.dcp_plan_export_dkv_segments(plan.handle, int(hkv), ctypes.byref(n), seg.ctypes.data_as(_lib.i32p)))
+    return int(n.value), seg
+
+
 # ------------------------------------------------------------------ launching calls (torch)
 def _dtype_code(t):
     import torch

@@ -122,9 +122,10 @@ extern "C" dcp_status_t dcp_plan_prepare(dcp_plan_t* plan, int32_t hq, int32_t h
   if ((st = static_scratch(&scratch_addr)) != DCP_OK) return st;
   if (plan->total_tokens == 0) return DCP_OK;
   DevGroup g;
-  if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g)) != DCP_OK) return st;
-  if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &g)) != DCP_OK) return st;
-  return plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &g, use_mfma ? hkv : 0);
+  const int n_seg = use_mfma ? xcd_segments(hkv) : 1;
+  if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g, 0, true, n_seg)) != DCP_OK) return st;
+  if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &g, 0, true, n_seg)) != DCP_OK) return st;
+  return plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &g, use_mfma ? hkv : 0, true, n_seg);
 }
 
 extern "C" dcp_status_t dcp_block_attn_fwd(dcp_plan_t* plan, const dcp_tensors_t* t, void* stream) {
@@ -144,7 +145,7 @@ extern "C" dcp_status_t dcp_block_attn_fwd(dcp_plan_t* plan, const dcp_tensors_t
   if (plan->has_window && plan->window <= 0) return fail(DCP_ERR_INVALID_ARG, "table has WINDOW rows but dcp_plan_set_window was not called");
   hipStream_t s = (hipStream_t)stream;
   DevGroup g;
-  if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g)) != DCP_OK) return st;
+  if ((st = plan->group_for(0, use_mfma ? mfma_fwd_tile() : scalar_fwd_tile(), s, &g, 0, true, use_mfma ? xcd_segments(t->hkv) : 1)) != DCP_OK) return st;
   KTensors k = pack(plan, t);
   ProfScope ps(DCP_K_FWD, s);
   return use_mfma ? mfma_fwd(g, k, s) : scalar_fwd(g, k, t->dtype, s);
@@ -198,7 +199,7 @@ static BwdWorkspace bwd_workspace(dcp_plan_t* plan, int32_t hq, int32_t hkv, int
   // range-bound summaries of every 32-row tile (+1 spare entry), only for tables with RANGES or WINDOW rows
   w.n_bounds = (plan->has_ranges || plan->has_window) ? ((size_t)plan->blk_t32.back() + 1) * 8 * sizeof(int32_t) : 0;
   w.n_bounds = (w.n_bounds + 255) & ~(size_t)255;
-  if (hkv > 0 && mfma_supports(dtype, d)) w.n_part = mfma_dkv_part_bytes(plan->host_items(2, mfma_dkv_tile(), hkv).n_pslots, hkv);
+  if (hkv > 0 && mfma_supports(dtype, d)) w.n_part = mfma_dkv_part_bytes(plan->host_items(2, mfma_dkv_tile(), hkv, xcd_segments(hkv)).n_pslots, hkv);
   return w;
 }
 
@@ -206,7 +207,7 @@ extern "C" dcp_status_t dcp_plan_export_dkv_items(dcp_plan_t* plan, int32_t hkv,
                                                   int64_t* n_items_out) {
   if (!plan || !n_items_out) return fail(DCP_ERR_INVALID_ARG, "plan or n_items_out is NULL");
   if (hkv <= 0) return fail(DCP_ERR_INVALID_ARG, "hkv must be positive");
-  const HostItems& hi = plan->host_items(2, mfma_dkv_tile(), hkv);
+  const HostItems& hi = plan->host_items(2, mfma_dkv_tile(), hkv, xcd_segments(hkv));
   *n_items_out = (int64_t)hi.items.size();
   if (dst) {
     if (capacity_rows < (int64_t)hi.items.size()) return fail(DCP_ERR_INVALID_ARG, "export capacity too small");
@@ -215,6 +216,15 @@ extern "C" dcp_status_t dcp_plan_export_dkv_items(dcp_plan_t* plan, int32_t hkv,
       dst[5 * i] = w.unit; dst[5 * i + 1] = w.tile; dst[5 * i + 2] = w.e0; dst[5 * i + 3] = w.e1; dst[5 * i + 4] = w.pslot;
     }
   }
+  return DCP_OK;
+}
+
+extern "C" dcp_status_t dcp_plan_export_dkv_segments(dcp_plan_t* plan, int32_t hkv, int32_t* n_seg_out, int32_t* seg_out) {
+  if (!plan || !n_seg_out || !seg_out) return fail(DCP_ERR_INVALID_ARG, "plan, n_seg_out or seg_out is NULL");
+  if (hkv <= 0) return fail(DCP_ERR_INVALID_ARG, "hkv must be positive");
+  const HostItems& hi = plan->host_items(2, mfma_dkv_tile(), hkv, xcd_segments(hkv));
+  *n_seg_out = hi.n_seg;
+  for (int k = 0; k <= 8; k++) seg_out[k] = hi.seg[k];
   return DCP_OK;
 }
 
@@ -250,8 +260,9 @@ dcp_status_t dcp::bwd_launch(dcp_plan_t* plan, const dcp_tensors_t* t, void* wor
   if (!workspace || workspace_bytes < need) return fail(DCP_ERR_WORKSPACE, "workspace is NULL or smaller than dcp_bwd_workspace_bytes");
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(DCP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
   DevGroup gq, gkv;
-  if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &gq, 0, may_alloc)) != DCP_OK) return st;
-  if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv, use_mfma ? t->hkv : 0, may_alloc)) != DCP_OK) return st;
+  const int n_seg = use_mfma ? xcd_segments(t->hkv) : 1;
+  if ((st = plan->group_for(1, use_mfma ? mfma_dq_tile() : scalar_bwd_tile(), s, &gq, 0, may_alloc, n_seg)) != DCP_OK) return st;
+  if ((st = plan->group_for(2, use_mfma ? mfma_dkv_tile() : scalar_bwd_tile(), s, &gkv, use_mfma ? t->hkv : 0, may_alloc, n_seg)) != DCP_OK) return st;
   KTensors k = pack(plan, t);
   const size_t n_hT = wsz.n_hT;
   k.part = (float*)((char*)workspace + 2 * wsz.n_hT + wsz.n_bounds);

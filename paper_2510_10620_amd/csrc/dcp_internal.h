@@ -61,12 +61,24 @@ struct DevGroup {
   const int32_t* ent_moff;   // [nnz]     offset of each row's other block
   const int32_t* ent_t32;    // [nnz]     index of the other block's first 32-row tile (range-bound summaries)
   const int32_t* ent_rec;    // [nnz][8]  the same per row in one record: start, len, kind, moff, t32, 0, 0, 0 (32-byte aligned)
-  const WorkItem* items;     // [n_items] longest first
+  const WorkItem* items;     // [n_items] longest first inside each segment
   const ReduceItem* reduce;  // [n_reduce] split (unit, tile)s, or null
   int32_t n_items;
   int32_t n_reduce;
   int32_t n_units;
+  // The work list in n_seg segments of about equal cost (n_seg = xcd_segments(KV heads): 1, 2, 4 or 8):
+  // segment s = items [seg[s], seg[s + 1]); entries past n_seg repeat n_items.
+  int32_t n_seg;
+  int32_t seg[9];
 };
+
+// Segments the work list is cut into so that (KV head, segment) pairs divide evenly among the 8 XCDs: one when the
+// KV heads are a multiple of 8 (an XCD takes whole heads), 8 when there is one KV head.
+inline int xcd_segments(int kv_heads) {
+  int g = 8;
+  while (kv_heads % g) g >>= 1;   // gcd(8, kv_heads)
+  return 8 / g;
+}
 
 struct HostGroup {
   std::vector<int32_t> unit_blk, unit_out, ptr, idx, ent_blk, ent_start, ent_len, ent_kind;
@@ -76,6 +88,8 @@ struct HostItems {
   std::vector<WorkItem> items;
   std::vector<ReduceItem> reduce;
   int32_t n_pslots = 0;
+  int32_t n_seg = 1;
+  int32_t seg[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
 };
 
 struct DevItems {
@@ -107,18 +121,19 @@ struct dcp_plan {
   int32_t* dev_arena = nullptr;
   dcp::DevGroup d_fwd{}, d_bwdq{}, d_bwdkv{};
   const int32_t *d_merge_ptr = nullptr, *d_merge_idx = nullptr, *d_slot_qblk = nullptr, *d_q_mem0 = nullptr, *d_blk_t32 = nullptr;
-  // (group id, tile rows, split heads) -> work list; split heads = 0: no splitting, else the number of workgroups
-  // launched per item (the long items are cut so that no workgroup outlasts the rest of the grid by much)
-  typedef std::tuple<int, int, int> ItemKey;
+  // (group id, tile rows, split heads, segments) -> work list; split heads = 0: no splitting, else the number of
+  // workgroups launched per item (the long items are cut so that no workgroup outlasts the rest of the grid by much);
+  // segments: see DevGroup
+  typedef std::tuple<int, int, int, int> ItemKey;
   std::map<ItemKey, dcp::HostItems> h_items;
   std::map<ItemKey, dcp::DevItems> items;
 
   // may_alloc = false: fail (DCP_ERR_INVALID_ARG) instead of creating a device copy that does not exist yet
   dcp_status_t ensure_device(hipStream_t stream, bool may_alloc = true);
   // group id: 0 fwd, 1 bwdq, 2 bwdkv.  Host only; takes the plan's lock.
-  const dcp::HostItems& host_items(int group_id, int tile_rows, int split_heads);
+  const dcp::HostItems& host_items(int group_id, int tile_rows, int split_heads, int n_seg = 1);
   dcp_status_t group_for(int group_id, int tile_rows, hipStream_t stream, dcp::DevGroup* out, int split_heads = 0,
-                         bool may_alloc = true);
+                         bool may_alloc = true, int n_seg = 1);
 };
 
 // Blockwise Copy list: validated entries cut into chunks of at most kCopyChunkRows rows.

@@ -38,6 +38,19 @@ __device__ __forceinline__ int4 range_row(const KTensors& t, int i, int s0) {
 }
 #endif
 
+// Grid of a launch whose workgroups find their work with decode_wg: 8 times the largest number of workgroups any XCD
+// needs for its (KV head, segment) units.
+inline int xcd_grid(const DevGroup& g, int heads_outer, int heads_inner) {
+  const int upx = (heads_outer * g.n_seg) / 8;
+  int most = 0;
+  for (int x = 0; x < 8; x++) {
+    int n = 0;
+    for (int u = x * upx; u < (x + 1) * upx; u++) n += (g.seg[u % g.n_seg + 1] - g.seg[u % g.n_seg]) * heads_inner;
+    most = n > most ? n : most;
+  }
+  return 8 * most;
+}
+
 // Optional per-kernel event timing (see dcp_profile_enable).
 struct ProfScope {
   int id;

@@ -70,9 +70,9 @@ int mfma_dkv_tile() { return 128; }
 
 dcp_status_t mfma_bwd_dkv(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
-  const int per_xcd = (g.n_items * t.hkv + 7) / 8;
-  if (t.masked) mfma_dkv_launch_ranges(g, t, per_xcd * 8, s);   // the variant for per-token ranges lives in its own file
-  else hipLaunchKernelGGL(mfma_dkv_kernel<false>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  const int grid = xcd_grid(g, t.hkv, 1);
+  if (t.masked) mfma_dkv_launch_ranges(g, t, grid, s);   // the variant for per-token ranges lives in its own file
+  else hipLaunchKernelGGL(mfma_dkv_kernel<false>, dim3(grid), dim3(256), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   if (g.n_reduce > 0) {
     hipLaunchKernelGGL(dkv_reduce_kernel, dim3(g.n_reduce, t.hkv), dim3(256), 0, s, g, t);

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(DevGroup g, KTensors t)
 
   int item, head;
   const int G = t.hq / t.hkv;
-  if (!decode_wg(g.n_items, t.hkv, G, &item, &head)) return;
+  if (!decode_wg(g, t.hkv, G, &item, &head)) return;
   const int hk = head / G;
   WorkItem w = g.items[item];
   w.unit = uni(w.unit); w.tile = uni(w.tile); w.e0 = uni(w.e0); w.e1 = uni(w.e1);
@@ -210,9 +210,9 @@ int mfma_dq_tile() { return 128; }
 
 dcp_status_t mfma_bwd_dq(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
-  const int per_xcd = (g.n_items * t.hq + 7) / 8;
-  if (t.masked) hipLaunchKernelGGL(mfma_dq_kernel<true>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
-  else hipLaunchKernelGGL(mfma_dq_kernel<false>, dim3(per_xcd * 8), dim3(256), 0, s, g, t);
+  const int grid = xcd_grid(g, t.hkv, t.hq / t.hkv);
+  if (t.masked) hipLaunchKernelGGL(mfma_dq_kernel<true>, dim3(grid), dim3(256), 0, s, g, t);
+  else hipLaunchKernelGGL(mfma_dq_kernel<false>, dim3(grid), dim3(256), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;
 }

@@ -280,7 +280,7 @@ __global__ __launch_bounds__(64 * kFwdWaves, (NQ == 1 ? 2 : 1)) void mfma_fwd_ke
 
   int item, head;
   const int G = t.hq / t.hkv;
-  if (!decode_wg(g.n_items, t.hkv, G, &item, &head)) return;
+  if (!decode_wg(g, t.hkv, G, &item, &head)) return;
   const int hk = head / G;
   WorkItem w = g.items[item];
   w.unit = uni(w.unit); w.tile = uni(w.tile); w.e0 = uni(w.e0); w.e1 = uni(w.e1);
@@ -472,10 +472,9 @@ int mfma_fwd_tile() { return FwdCfg<DCP_FWD_NQ>::kTileM; }
 
 dcp_status_t mfma_fwd(const DevGroup& g, const KTensors& t, hipStream_t s) {
   if (g.n_items == 0) return DCP_OK;
-  const int total = g.n_items * t.hq;
-  const int per_xcd = (total + 7) / 8;
-  if (t.masked) hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, true>), dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
-  else hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, false>), dim3(per_xcd * 8), dim3(64 * kFwdWaves), 0, s, g, t);
+  const int grid = xcd_grid(g, t.hkv, t.hq / t.hkv);
+  if (t.masked) hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, true>), dim3(grid), dim3(64 * kFwdWaves), 0, s, g, t);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<DCP_FWD_NQ, false>), dim3(grid), dim3(64 * kFwdWaves), 0, s, g, t);
   DCP_HIP_TRY(hipGetLastError());
   return DCP_OK;
 }

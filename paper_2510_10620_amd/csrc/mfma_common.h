@@ -381,18 +381,26 @@ __device__ __forceinline__ int classify32(int kind, int ks, int c1, int q_lo, in
   return (whole && rb.all_see(ks, ke)) ? kFull : kPartial;
 }
 
-// XCD-aware decode of the flat workgroup id: the grid is cut into 8 contiguous chunks of the
-// work order (kv head major, then item, then query head inside the group); chunk x runs on XCD x
-// because consecutive workgroup ids are dealt round-robin to the 8 XCDs.
-__device__ __forceinline__ bool decode_wg(int n_items, int heads_outer, int heads_inner, int* item, int* head) {
-  const int total = n_items * heads_outer * heads_inner;
-  const int per_xcd = (total + 7) >> 3;
-  const int w = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if ((int)(blockIdx.x >> 3) >= per_xcd || w >= total) return false;
-  const int hi = w % heads_inner;
-  *item = (w / heads_inner) % n_items;
-  *head = (w / (heads_inner * n_items)) * heads_inner + hi;
-  return true;
+// XCD-aware decode of the flat workgroup id.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, so
+// workgroup id b is the (b / 8)-th of XCD b % 8.  The work is cut into (KV head, segment of the work list) units,
+// heads_outer * n_seg of them, a multiple of 8; XCD x takes units x * U / 8 .. in (head, segment) order and walks
+// each in (item, head of the group) order: workgroups that run at the same time on an XCD work on neighbouring
+// items of one KV head, whose K / V (or Q / dO) rows that XCD's L2 then holds once.  With a multiple of 8 KV heads
+// an XCD takes whole heads and the list is one segment.
+__device__ __forceinline__ bool decode_wg(const DevGroup& g, int heads_outer, int heads_inner, int* item, int* head) {
+  const int upx = (heads_outer * g.n_seg) >> 3;
+  int p = blockIdx.x >> 3;
+  for (int u = (blockIdx.x & 7) * upx, ue = u + upx; u < ue; u++) {
+    const int s = u % g.n_seg;
+    const int s0 = g.seg[s], len = (g.seg[s + 1] - s0) * heads_inner;
+    if (p < len) {
+      *item = s0 + p / heads_inner;
+      *head = (u / g.n_seg) * heads_inner + p % heads_inner;
+      return true;
+    }
+    p -= len;
+  }
+  return false;
 }
 
 }  // namespace dcp

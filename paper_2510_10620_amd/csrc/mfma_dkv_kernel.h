@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(DevGroup g, KTensors t
   __shared__ __attribute__((aligned(1024))) char stages[2 * kStageBytes];   // double buffer
 
   int item, hk;
-  if (!decode_wg(g.n_items, t.hkv, 1, &item, &hk)) return;
+  if (!decode_wg(g, t.hkv, 1, &item, &hk)) return;
   const int G = t.hq / t.hkv;
   WorkItem w = g.items[item];
   w.unit = uni(w.unit); w.tile = uni(w.tile); w.e0 = uni(w.e0); w.e1 = uni(w.e1); w.pslot = uni(w.pslot);

@@ -563,9 +563,9 @@ static int64_t tile_cost(int32_t kind, int64_t r0, int64_t r1, int64_t c0, int64
 static constexpr int64_t kResidentWorkgroups = 512;
 static constexpr int32_t kMaxParts = 64;
 
-const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
+const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads, int n_seg) {
   std::lock_guard<std::mutex> lock(mu);
-  const ItemKey key(gid, tile_rows, split_heads);
+  const ItemKey key(gid, tile_rows, split_heads, n_seg);
   auto hit = h_items.find(key);
   if (hit != h_items.end()) return hit->second;
   HostGroup* hg = gid == 0 ? &fwd : (gid == 1 ? &bwdq : &bwdkv);
@@ -691,6 +691,46 @@ const HostItems& dcp_plan::host_items(int gid, int tile_rows, int split_heads) {
     });
     if ((double)play(by_seq) <= 1.01 * (double)play(sc)) sc.swap(by_seq);
   }
+  hi.n_seg = n_seg;
+  for (int s = 0; s <= 8; s++) hi.seg[s] = (int32_t)sc.size();
+  hi.seg[0] = 0;
+  if (n_seg > 1 && !sc.empty()) {
+    // With fewer KV heads than a multiple of 8 an XCD takes a part of a head's list, and contiguous parts of a list
+    // that runs from the longest item to the shortest are anything but equal.  The list is dealt into n_seg segments
+    // of about equal cost, the order inside a segment kept: first the sequences that are at most half a segment, whole
+    // (their tiles read the same K / V or Q / dO rows and are better off in one XCD's L2), costliest first, then the
+    // items of the larger sequences one by one, which level the segments out; each goes to the segment that holds
+    // least so far.
+    std::vector<int64_t> seq_cost(n_seq, 0);
+    int64_t sum = 0;
+    for (const Scored& x : sc) { seq_cost[blk_seq[hg->unit_blk[x.w.unit]]] += x.cost; sum += x.cost; }
+    const int64_t half = std::max<int64_t>(1, sum / n_seg / 2);
+    std::vector<int64_t> load(n_seg, 0);
+    std::vector<int32_t> bin(sc.size(), 0), seq_bin(n_seq, -1);
+    auto lightest = [&]() { return (int32_t)(std::min_element(load.begin(), load.end()) - load.begin()); };
+    std::vector<int32_t> small;
+    for (int32_t q = 0; q < n_seq; q++)
+      if (seq_cost[q] > 0 && seq_cost[q] <= half) small.push_back(q);
+    std::stable_sort(small.begin(), small.end(), [&](int32_t a, int32_t b) { return seq_cost[a] > seq_cost[b]; });
+    for (int32_t q : small) { seq_bin[q] = lightest(); load[seq_bin[q]] += seq_cost[q]; }
+    std::vector<size_t> big;
+    for (size_t i = 0; i < sc.size(); i++)
+      if (seq_cost[blk_seq[hg->unit_blk[sc[i].w.unit]]] > half) big.push_back(i);
+    std::stable_sort(big.begin(), big.end(), [&](size_t a, size_t b) { return sc[a].cost > sc[b].cost; });
+    for (size_t i : big) { bin[i] = lightest(); load[bin[i]] += sc[i].cost; }
+    for (size_t i = 0; i < sc.size(); i++) {
+      const int32_t q = blk_seq[hg->unit_blk[sc[i].w.unit]];
+      if (seq_bin[q] >= 0) bin[i] = seq_bin[q];
+    }
+    std::vector<Scored> dealt;
+    dealt.reserve(sc.size());
+    for (int s = 0; s < n_seg; s++) {
+      for (size_t i = 0; i < sc.size(); i++)
+        if (bin[i] == s) dealt.push_back(sc[i]);
+      hi.seg[s + 1] = (int32_t)dealt.size();
+    }
+    sc.swap(dealt);
+  }
   hi.items.resize(sc.size());
   for (size_t i = 0; i < sc.size(); i++) hi.items[i] = sc[i].w;
   return h_items.emplace(key, std::move(hi)).first->second;
@@ -711,13 +751,14 @@ static dcp_status_t upload(const std::vector<T>& v, T** dev, hipStream_t stream)
   return DCP_OK;
 }
 
-dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, DevGroup* out, int split_heads, bool may_alloc) {
+dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, DevGroup* out, int split_heads, bool may_alloc,
+                                 int n_seg) {
   dcp_status_t st = ensure_device(stream, may_alloc);
   if (st != DCP_OK) return st;
-  const HostItems& hi = host_items(gid, tile_rows, split_heads);
+  const HostItems& hi = host_items(gid, tile_rows, split_heads, n_seg);
   std::lock_guard<std::mutex> lock(mu);
   DevGroup dg = gid == 0 ? d_fwd : (gid == 1 ? d_bwdq : d_bwdkv);
-  const ItemKey key(gid, tile_rows, split_heads);
+  const ItemKey key(gid, tile_rows, split_heads, n_seg);
   auto it = items.find(key);
   if (it == items.end()) {
     if (!may_alloc) return fail(DCP_ERR_INVALID_ARG, "the plan has no work list for this shape yet: call dcp_plan_prepare first");
@@ -735,6 +776,8 @@ dcp_status_t dcp_plan::group_for(int gid, int tile_rows, hipStream_t stream, Dev
   dg.n_items = it->second.n_items;
   dg.reduce = it->second.reduce;
   dg.n_reduce = it->second.n_reduce;
+  dg.n_seg = hi.n_seg;
+  for (int k = 0; k <= 8; k++) dg.seg[k] = hi.seg[k];
   *out = dg;
   return DCP_OK;
 }

@@ -46,6 +46,9 @@ long fake_rows_walked() { return g_rows_walked; }
 // own_rows / other_rows: extents of the tensors on the unit's side and on the other side.
 static dcp_status_t walk_group(const DevGroup& g, int tile_rows, int64_t own_rows, int64_t other_rows, int32_t n_slots,
                                int32_t block_size, bool reduce_list) {
+  // the segments of the work list cover it in order
+  WALK_CHECK(g.n_seg >= 1 && g.n_seg <= 8 && g.seg[0] == 0 && g.seg[g.n_seg] == g.n_items, "work-list segments do not cover the list");
+  for (int s = 0; s < 8; s++) WALK_CHECK(g.seg[s] <= g.seg[s + 1], "work-list segments not in order");
   for (int32_t i = 0; i < g.n_items; i++) {
     const WorkItem w = g.items[i];
     WALK_CHECK(w.unit >= 0 && w.unit < g.n_units, "work item names a unit out of range");

@@ -160,6 +160,47 @@ def test_dkv_work_list_is_an_exact_partition(spec, lens, B, hkv):
     assert full - base == len(slots) * hkv * 2 * 128 * 128 * 4
 
 
+@pytest.mark.parametrize("hkv", [1, 2, 3, 4, 6, 8, 12, 16])
+def test_dkv_work_list_segments_balance_the_xcds(hkv):
+    """With KV heads that are no multiple of 8 an XCD takes (KV head, segment) pairs: the segments must cover the work
+    list in order, keep every sequence that is small against a segment in one of them, and hold about equal numbers
+    of visible (query, key) pairs (counted here from the sequence lengths: a causal key tile is seen by the queries
+    from its first key on)."""
+    w = W.make_workload(2)                      # 65 536 causal tokens in 23 sequences of 512 .. 12 K
+    cu, B = w.cu_seqlens, w.block_size
+    table = P.dcp_build_block_table(cu, B, w.ranges)
+    plan = P.dcp_plan_create(cu, B, table)
+    items = P.dcp_plan_export_dkv_items(plan, hkv)
+    n_seg, seg = P.dcp_plan_export_dkv_segments(plan, hkv)
+    assert n_seg == 8 // np.gcd(8, hkv)
+    assert seg[0] == 0 and seg[n_seg] == len(items) and np.all(np.diff(seg) >= 0) and np.all(seg[n_seg:] == len(items))
+    if n_seg == 1:
+        return
+    blk_start, blk_len, blk_seq = plan.export("BLK_START"), plan.export("BLK_LEN"), plan.export("BLK_SEQ")
+    ptr, idx = plan.export("BWDKV_PTR"), plan.export("BWDKV_IDX")
+    kv_of_unit = [u for u in range(len(blk_len))]            # BWDKV CSR: unit = kv_blk
+    cost = np.zeros(len(items))
+    seq_of = np.zeros(len(items), dtype=np.int64)
+    for i, (u, t, e0, e1, ps) in enumerate(items.tolist()):
+        kb = kv_of_unit[u]
+        k0 = blk_start[kb] + 128 * t
+        k1 = min(k0 + 128, blk_start[kb] + blk_len[kb])
+        seq_of[i] = blk_seq[kb]
+        for e in range(e0, e1):
+            qb = table[idx[e], 0]
+            q0, q1 = blk_start[qb], blk_start[qb] + blk_len[qb]
+            ks = np.arange(k0, k1)
+            cost[i] += np.sum(q1 - np.maximum(q0, ks)) if table[idx[e], 2] == P.DCP_MASK_CAUSAL else (q1 - q0) * (k1 - k0)
+    per_seg = np.array([cost[seg[s]:seg[s + 1]].sum() for s in range(n_seg)])
+    assert per_seg.max() <= 1.10 * per_seg.mean(), per_seg / per_seg.mean()
+    # sequences that are at most half a segment stay whole
+    seq_cost = np.bincount(seq_of, weights=cost)
+    seg_of_item = np.searchsorted(seg[1:n_seg + 1], np.arange(len(items)), side="right")
+    for q in np.unique(seq_of):
+        if seq_cost[q] <= 0.45 * per_seg.mean():
+            assert len(set(seg_of_item[seq_of == q])) == 1, f"sequence {q} is spread over several segments"
+
+
 @pytest.mark.parametrize("window,sink", [(50, 0), (40, 7), (16, 16), (1, 0), (300, 3), (5, 400)])
 def test_window_table_and_pair_counts_bit_exact_vs_oracle(window, sink):
     rng = np.random.default_rng(29)
