@@ -109,9 +109,11 @@ def test_shapes_only_the_scalar_family_covers(dtype, d):
     run_case(w, H.oracle_table(w), IMPLS["auto"], label=f"{dtype}/D{d}")
 
 
-@pytest.mark.parametrize("hq,hkv", [(2, 2), (8, 1), (6, 2)])
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (8, 1), (6, 2), (6, 3), (12, 12), (16, 16)])
 def test_head_group_sizes(hq, hkv):
-    """Query heads per KV head other than the benchmark's 4: 1 (no sharing), 8 and 3 (not a power of two)."""
+    """Query heads per KV head other than the benchmark's 4: 1 (no sharing), 8 and 3 (not a power of two); and KV head
+    counts that divide the work among the XCDs in every way there is: 1, 2 and 3 (lists in 8, 4 and 8 segments,
+    one, one and three (head, segment) pairs per XCD), 12 (two segments, three pairs) and 16 (two whole heads)."""
     w = W.custom_workload("groups", [333, 200], 128, hq, hkv, 128, "bf16", W.MaskSpec("lambda", window=90, sink=9), seed=35,
                           input_scale=0.5)
     run_case(w, H.oracle_table(w), IMPLS["auto"], label=f"hq{hq}/hkv{hkv}")
