@@ -233,6 +233,9 @@ def main():
         extra["blockwise_copy"] = copy_section(torch, P, np, plan, q, steps=max(3, args.steps // 2))
         extra["gradient_sum"] = sum_section(torch, P, q, steps=max(3, args.steps // 2))
         extra["short_sequences"] = short_section(torch, P, W, np, steps=5)
+        # config 2's batch with the heads of an 8-way tensor-parallel shard: the KV heads no longer divide among the 8
+        # XCDs as whole heads, the work lists are dealt into balanced segments instead
+        extra["fewer_heads"] = short_section(torch, P, W, np, steps=5, heads=(4, 1), lens=np.diff(w.cu_seqlens))
         extra["other_masks"] = masks_section(torch, P, W, np, steps=3)
         extra["execution_plan"] = executor_section(torch, P, W, np, steps=3)
 
@@ -461,11 +464,13 @@ def masks_section(torch, P, W, np, steps):
     return res
 
 
-def short_section(torch, P, W, np, steps, seq_len=1024, tokens=65536):
+def short_section(torch, P, W, np, steps, seq_len=1024, tokens=65536, heads=(32, 8), lens=None):
     """The headline step on a batch of short sequences: the same 65 536 tokens, heads and block size as config 2, cut
     into equal causal sequences of 1 024 tokens (the short end of the paper's length-scale 0.5 batches, Sec. 7.1):
-    every work item is a handful of key tiles long, so the fixed cost of a work item shows."""
-    w = W.custom_workload("causal_short", [seq_len] * (tokens // seq_len), 1024, 32, 8, 128, "bf16", W.MaskSpec("causal"), seed=109,
+    every work item is a handful of key tiles long, so the fixed cost of a work item shows.
+    lens: other sequence lengths; heads: other (query, KV) head counts (what a tensor-parallel shard would hold)."""
+    lens = [seq_len] * (tokens // seq_len) if lens is None else [int(x) for x in lens]
+    w = W.custom_workload("causal_short", lens, 1024, heads[0], heads[1], 128, "bf16", W.MaskSpec("causal"), seed=109,
                           input_scale=1.0 / np.sqrt(128))
     table = P.dcp_build_block_table(w.cu_seqlens, w.block_size, w.ranges)
     pairs = int(P.dcp_count_pairs(w.cu_seqlens, w.block_size, table, w.ranges).sum())
@@ -491,7 +496,8 @@ def short_section(torch, P, W, np, steps, seq_len=1024, tokens=65536):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
     unit = pairs * w.hq * w.d
-    res = dict(workload=f"{tokens} tokens in {tokens // seq_len} causal sequences of {seq_len}, {w.hq}/{w.hkv} heads, D {w.d}",
+    shape = f"{len(lens)} causal sequences of {seq_len}" if len(set(lens)) == 1 else f"{len(lens)} causal sequences of {min(lens)} .. {max(lens)}"
+    res = dict(workload=f"{sum(lens)} tokens in {shape}, {w.hq}/{w.hkv} heads, D {w.d}",
                visible_pairs=pairs, ms_per_step=round(ms, 4), tflops=round(14 * unit / (ms * 1e-3) / 1e12, 1))
     for name, f in (("fwd", 4), ("dq", 4), ("dkv", 6)):
         tot, n = P.dcp_profile_read(name)
