@@ -569,6 +569,47 @@ def test_two_runs_are_bit_identical():
                                runs[1][n].view(torch.int16 if n != "lse" else torch.int32)), f"{label}: {n} differs between two runs"
 
 
+def test_dv_of_a_sink_key_is_the_sum_with_p_rounded_to_bf16():
+    """Where the plain bound on dV is tight: a sink key under a small window is seen by every later query of every head
+    of its group (here 447 x 4), each with a weight near 1 / 8, and P goes into the dV product as bf16.  The rounding
+    of P, 2^-9 relative per term, then adds up over a sum whose root sum of squares is larger than the sum itself.  The
+    kernel's value must be that sum exactly: P from the oracle's scores and LSE, rounded to bf16 (nearest even), times
+    dO, summed in fp64, then rounded to bf16 once -- to one bf16 step (scores in fp32 against fp64 can turn a rounding
+    of P the other way)."""
+    w = W.custom_workload("sink", [447, 26], 256, 8, 2, 128, "bf16", W.MaskSpec("lambda", window=7, sink=1), seed=433, input_scale=0.5)
+    table = H.oracle_table(w)
+    tensors = W.make_tensors(w)
+    g = H.GpuRun(w, tensors, table, impl=IMPLS["auto"])
+    out, lse = g.forward()
+    dq, dk, dv = g.backward()
+    got = dict(out=out, lse=lse, dq=dq, dk=dk, dv=dv)
+    ref = H.oracle_full(w, tensors, table)
+    # everything but the sink key's dV row at the usual bound (that row is put aside for the comparison below)
+    rest = dict(got, dv=got["dv"].copy())
+    rest["dv"][0] = ref["dv"][0]
+    H.check(w, rest, ref, ALL, "sink key, all but the sink's dV")
+    q, k, do = (W.to_f64(w, tensors[n]) for n in ("q", "k", "dout"))
+    vis = OB.Visibility(w.cu_seqlens, w.block_size, table, w.ranges)
+    G = w.hq // w.hkv
+    L = 447
+    M = np.asarray(vis.rows(0, 0, L)).astype(bool)
+    assert M[:, 0].all()                                     # every query of the sequence sees its first token
+    worst_plain = worst_emul = 0.0
+    for kvh in range(w.hkv):
+        emul = np.zeros(w.d)
+        for h in range(G * kvh, G * kvh + G):
+            s_col = (q[:L, h] @ k[0, kvh]) * w.softmax_scale
+            p = np.exp(s_col - ref["lse"][h, :L])
+            p16 = W.bf16_bits_to_f64(W.f32_to_bf16_bits(p.astype(np.float32)))
+            emul += p16 @ do[:L, h]
+        step = 2.0 ** -7 * np.maximum(1.0, 2.0 ** np.floor(np.log2(np.maximum(np.abs(emul), 1e-30))))   # one bf16 step at |emul|
+        d_emul = np.abs(got["dv"][0, kvh] - emul)
+        assert (d_emul <= step).all(), f"kv head {kvh}: {d_emul.max():.4f} from the sum with bf16 P"
+        worst_emul = max(worst_emul, d_emul.max())
+        worst_plain = max(worst_plain, np.abs(got["dv"][0, kvh] - ref["dv"][0, kvh]).max())
+    print(f"sink key dV: max |kernel - exact| {worst_plain:.4f}, max |kernel - sum with bf16 P| {worst_emul:.4f}")
+
+
 def test_step_replays_from_a_hip_graph():
     """With a prepared plan the forward, the merge and the backward only launch kernels (no allocation, no
     synchronisation, no memset node), so a caller can record the step in a HIP graph.  Recorded once here, on a case
