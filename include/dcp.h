@@ -13,6 +13,8 @@
  *     enqueue work on it and return without synchronising, with one exception: the first launch
  *     that uses a plan (or a copy list) on a device uploads its integer arrays, which allocates
  *     device memory and waits for the stream once; dcp_plan_prepare does that ahead of time.
+ *     A launch writes nothing into the plan: several streams may run one (prepared) plan at the same time on
+ *     tensors and workspaces of their own.
  *   - Tensors: q, out, dout, dq are [T, Hq, D]; k, v, dk, dv are [T, Hkv, D]; D is contiguous;
  *     token and head strides are given in elements.  lse and delta are float [Hq, T] contiguous.
  *     Query head h reads KV head h / (Hq / Hkv).  T = cu_seqlens[n_seq] packed tokens.

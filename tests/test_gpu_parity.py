@@ -569,6 +569,56 @@ def test_two_runs_are_bit_identical():
                                runs[1][n].view(torch.int16 if n != "lse" else torch.int32)), f"{label}: {n} differs between two runs"
 
 
+def test_two_streams_share_a_plan():
+    """A plan holds nothing a launch writes (work lists and table are read-only on the device; partial sums, delta and
+    LSE copies live in the caller's workspace), so two streams may run the same plan at the same time on tensors of
+    their own.  Two forward + backward passes on different inputs, enqueued on two streams without a wait between
+    them, must give the bits of the same passes run one after the other."""
+    import torch
+    import paper_2510_10620_amd as P
+    lens = W.draw_lengths(8192, "lognormal", 512, 4096, seed=2, median=1024)
+    w = W.custom_workload("streams", lens, 256, 8, 2, 128, "bf16", W.MaskSpec("causal"), seed=59, input_scale=1.0 / np.sqrt(128))
+    table = H.oracle_table(w)
+    plan = P.dcp_plan_create(w.cu_seqlens, w.block_size, table)
+    P.dcp_plan_prepare(plan, w.hq, w.hkv, w.d, P.DCP_BF16)
+    need = max(256, P.dcp_bwd_workspace_bytes(plan, w.hq, w.hkv, w.d, P.DCP_BF16))
+    T = w.total_tokens
+    sets = []
+    for i in range(2):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(100 + i)
+        mk = lambda h, sc: (torch.randn((T, h, w.d), device="cuda", generator=gen) * sc).to(torch.bfloat16)
+        q, k, v, do = mk(w.hq, w.input_scale), mk(w.hkv, w.input_scale), mk(w.hkv, w.input_scale), mk(w.hq, 1.0)
+        bufs = dict(out=torch.empty_like(q), lse=torch.empty((w.hq, T), dtype=torch.float32, device="cuda"),
+                    dq=torch.empty_like(q), dk=torch.empty_like(k), dv=torch.empty_like(v))
+        sets.append(dict(q=q, k=k, v=v, do=do, bufs=bufs, ws=torch.empty(need, dtype=torch.uint8, device="cuda")))
+
+    def run(s):
+        b = s["bufs"]
+        P.dcp_block_attn_fwd(plan, s["q"], s["k"], s["v"], b["out"], b["lse"], w.softmax_scale, None)
+        P.dcp_block_attn_bwd(plan, s["q"], s["k"], s["v"], b["out"], b["lse"], s["do"], b["dq"], b["dk"], b["dv"],
+                             w.softmax_scale, s["ws"], None)
+
+    for s in sets:                                   # one after the other, on the current stream
+        run(s)
+    torch.cuda.synchronize()
+    ref = [{n: t.clone() for n, t in s["bufs"].items()} for s in sets]
+    for s in sets:
+        for t in s["bufs"].values():
+            t.fill_(float("nan"))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):                             # interleaved so that the launches of the two streams overlap
+        for s, st in zip(sets, streams):
+            with torch.cuda.stream(st):
+                run(s)
+    torch.cuda.synchronize()
+    for i, s in enumerate(sets):
+        for n in ALL:
+            view = torch.int32 if n == "lse" else torch.int16
+            assert torch.equal(s["bufs"][n].view(view), ref[i][n].view(view)), f"stream {i}: {n} differs from the sequential run"
+
+
 def test_dv_of_a_sink_key_is_the_sum_with_p_rounded_to_bf16():
     """Where the plain bound on dV is tight: a sink key under a small window is seen by every later query of every head
     of its group (here 447 x 4), each with a weight near 1 / 8, and P goes into the dV product as bf16.  The rounding
