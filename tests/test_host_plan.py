@@ -28,6 +28,14 @@ def test_library_exports_every_declared_symbol():
     assert P.dcp_version().startswith("dcp_attn")
 
 
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: asked for more it must say so and exit, before it touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
 def _oracle_table(spec, cu, B):
     return OB.table_from_mask(lambda s, L, r0, r1: OM.dense_rows(spec, L, r0, r1), cu, B)
 
