@@ -85,8 +85,37 @@ static dcp_status_t build_table(const Partition& p, int32_t n_seq, const int32_t
   for (int32_t s = 0; s < n_seq; s++) {
     for (int32_t qb = p.first[s]; qb < p.first[s + 1]; qb++) {
       int64_t q0 = p.start[qb], q1 = q0 + p.len[qb];
+      // Bounds of the block's rows, per range: most KV blocks are settled by them (no row's range reaches the block:
+      // no entry; one range of every row covers it: NONE) and only the blocks on a mask edge need the rows themselves.
+      int64_t smin[2] = {INT64_MAX, INT64_MAX}, smax[2] = {INT64_MIN, INT64_MIN};
+      int64_t emin[2] = {INT64_MAX, INT64_MAX}, emax[2] = {INT64_MIN, INT64_MIN};
+      bool every[2] = {true, true};   // every row has this range non-empty
+      for (int64_t i = q0; i < q1; i++)
+        for (int k = 0; k < 2; k++) {
+          const int64_t lo = ranges[4 * i + 2 * k], hi = ranges[4 * i + 2 * k + 1];
+          if (hi > lo) {
+            smin[k] = std::min(smin[k], lo); smax[k] = std::max(smax[k], lo);
+            emin[k] = std::min(emin[k], hi); emax[k] = std::max(emax[k], hi);
+          } else {
+            every[k] = false;
+          }
+        }
       for (int32_t kb = p.first[s]; kb < p.first[s + 1]; kb++) {
         int64_t c0 = p.start[kb], c1 = c0 + p.len[kb];
+        const bool out0 = emax[0] == INT64_MIN || c0 >= emax[0] || c1 <= smin[0];   // no row's first range reaches the block
+        const bool out1 = emax[1] == INT64_MIN || c0 >= emax[1] || c1 <= smin[1];
+        if (out0 && out1) continue;
+        bool covered = false;
+        for (int k = 0; k < 2; k++) covered |= every[k] && smax[k] <= c0 && emin[k] >= c1;
+        if (covered) {
+          if (table_out && n < capacity) {
+            table_out[3 * n + 0] = qb;
+            table_out[3 * n + 1] = kb;
+            table_out[3 * n + 2] = DCP_MASK_NONE;
+          }
+          n++;
+          continue;
+        }
         bool any = false, all = true, causal = true;
         for (int64_t i = q0; i < q1; i++) {
           const int32_t* r = ranges + 4 * i;

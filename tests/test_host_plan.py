@@ -28,6 +28,40 @@ def test_library_exports_every_declared_symbol():
     assert P.dcp_version().startswith("dcp_attn")
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_block_table_from_arbitrary_ranges_bit_exact_vs_oracle(seed):
+    """Range arrays no mask family produces: per token two random ranges inside its sequence, either of them possibly
+    empty, overlapping, the second before the first, and blocks of rows that all see a whole KV block through one range
+    or through none (the cases the generator settles from the bounds of a block's rows without looking at the rows)."""
+    rng = np.random.default_rng(500 + seed)
+    lens = [int(x) for x in rng.integers(1, 260, size=4)]
+    B = int(rng.choice([8, 16, 32]))
+    cu = W.cu_from_lengths(lens)
+    T = int(cu[-1])
+    ranges = np.zeros((T, 4), dtype=np.int32)
+    dense = {}
+    for s, L in enumerate(lens):
+        s0 = int(cu[s])
+        m = np.zeros((L, L), dtype=bool)
+        base = rng.integers(0, L + 1, size=4)              # a block-wide pattern, so that whole blocks are covered or missed
+        for i in range(L):
+            r = np.sort(rng.integers(0, L + 1, size=2)), np.sort(rng.integers(0, L + 1, size=2))
+            mode = int(rng.integers(0, 4))
+            if mode == 0:                                  # the shared pattern
+                r = np.sort(base[:2]), np.sort(base[2:])
+            elif mode == 1:                                # first range empty
+                r = (np.array([0, 0]), r[1])
+            elif mode == 2:                                # everything through one range
+                r = (np.array([0, L]), np.array([0, 0]))
+            for k in range(2):
+                ranges[s0 + i, 2 * k], ranges[s0 + i, 2 * k + 1] = s0 + r[k][0], s0 + r[k][1]
+                m[i, r[k][0]:r[k][1]] = True
+        dense[s] = m
+    want = OB.table_from_mask(lambda s, L, r0, r1: dense[s][r0:r1], cu, B)
+    got = P.dcp_build_block_table(cu, B, ranges)
+    assert np.array_equal(got, want)
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py measures one GPU: asked for more it must say so and exit, before it touches a device."""
     import subprocess
