@@ -140,21 +140,24 @@ def max_abs(a, b):
 
 
 def err_stats(a, b, knee, by_row=False):
-    """Errors of a against the reference b, split at |b| = knee: `raw` the largest |a - b| anywhere, `low` the largest
+    """Errors of a against the reference b, split at |b| = knee: `raw` the largest |a - b| anywhere, `rms` its root mean
+    square, `low` the largest
     |a - b| where |b| < knee, `high_rel` the largest |a - b| / |b| where |b| >= knee, `max_ref` the largest |b|.
     by_row: the magnitude that decides the side and divides the error is the largest |b| of the element's row
     (last axis) instead of the element's own."""
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
     cmp = _cmp_mask(a, b)
     if not cmp.any():
-        return dict(raw=0.0, low=0.0, high_rel=0.0, max_ref=0.0)
+        return dict(raw=0.0, low=0.0, high_rel=0.0, max_ref=0.0, rms=0.0)
     mag = np.abs(b)
     if by_row:
         mag = np.broadcast_to(np.where(np.isfinite(mag), mag, 0.0).max(axis=-1, keepdims=True), b.shape)
     d = np.nan_to_num(np.abs(a[cmp] - b[cmp]), nan=np.inf, posinf=np.inf)
     m = mag[cmp]
     lo, hi = m < knee, m >= knee
+    fin = np.isfinite(d)
     return dict(raw=float(d.max()), low=float(d[lo].max()) if lo.any() else 0.0,
+                rms=float(np.sqrt(np.mean(d[fin] ** 2))) if fin.any() else 0.0,
                 high_rel=float((d[hi] / m[hi]).max()) if hi.any() else 0.0,
                 max_ref=float(np.where(np.isfinite(np.abs(b[cmp])), np.abs(b[cmp]), 0.0).max()))
 
@@ -191,7 +194,7 @@ def check(w, got, ref, names, label="", verbose=True, by_row=()):
             continue
         st = err_stats(got[n], ref[n], tol["knee"], n in by_row)
         errs[n] = st["raw"]
-        lines.append(f"{n}{' [by row]' if n in by_row else ''} raw {st['raw']:.2e} (|ref|<{tol['knee']:g}: {st['low']:.2e}; above: rel {st['high_rel']:.2e}; max|ref| {st['max_ref']:.3g})")
+        lines.append(f"{n}{' [by row]' if n in by_row else ''} raw {st['raw']:.2e} rms {st['rms']:.1e} (|ref|<{tol['knee']:g}: {st['low']:.2e}; above: rel {st['high_rel']:.2e}; max|ref| {st['max_ref']:.3g})")
         assert st["low"] <= tol["o"], f"{label} {n}: max abs err {st['low']:.3e} > {tol['o']:.1e} where |ref| < {tol['knee']:g}"
         assert st["high_rel"] <= tol["rel"], f"{label} {n}: relative err {st['high_rel']:.3e} > {tol['rel']:.1e} where |ref| >= {tol['knee']:g}"
         if n not in by_row and st["max_ref"] > 0:
