@@ -94,7 +94,7 @@ static void one_case(Rng& r, int iter) {
   for (int64_t e = 0; e < n; e++)
     if (rnd(r, 0, 3) != 0) sub.insert(sub.end(), table.begin() + 3 * e, table.begin() + 3 * e + 3);
   const int64_t ns = (int64_t)sub.size() / 3;
-  const bool slots = rnd(r, 0, 1) == 1;
+  const bool slots = rnd(r, 0, 1) == 1 && ns > 0;   // (an empty share has no row to give a slot to)
   std::vector<int32_t> out_slot;
   int32_t n_slots = 0;
   if (slots) {   // (division, q_blk) -> slot
